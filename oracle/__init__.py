@@ -1,0 +1,23 @@
+"""CPU oracle for C = alpha*A*B + beta*C.  TEST INFRASTRUCTURE ONLY.
+
+This package is the checker that the GPU library is compared against; it is
+never part of the product path.  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import it, and it imports nothing from the
+GPU package.
+
+The arithmetic lives in ``ref_gemm.c`` (a triple loop in fp64 / int64 that
+follows the definition of the product in the paper's Sec. II-A and the
+alpha/beta form of its reference micro-kernel).  This module only compiles
+that file with gcc and marshals numpy arrays into it.
+"""
+from .ref import (  # noqa: F401
+    build,
+    num_threads,
+    half_to_double,
+    gemm_f32,
+    gemm_f16,
+    gemm_i8,
+    gemm_sample,
+    wrap_int32,
+    normalised_error,
+)

@@ -1,0 +1,149 @@
+"""ctypes loader for the CPU oracle (``ref_gemm.c``).  TEST INFRASTRUCTURE ONLY.
+
+Nothing here does arithmetic of the method except ``wrap_int32`` (reduction of
+the exact int64 result modulo 2^32, the int8 contract) and
+``normalised_error`` (the acceptance metric max|C - C_ref| / (K max|A| max|B|)).
+Arrays are numpy, host memory.  ``layout`` is "col" or "row"; a matrix is passed
+as the 1-D or 2-D numpy buffer that holds it plus its leading dimension.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ref_gemm.c")
+_LIB = os.path.join(_HERE, "libref_gemm.so")
+_lib = None
+
+_LAYOUT = {"col": 0, "row": 1}
+
+
+def build(force=False):
+    """Compile ref_gemm.c into libref_gemm.so next to it (gcc -O2 -fopenmp)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, f32, i32, vp, dbl = (ctypes.c_int64, ctypes.c_float, ctypes.c_int32,
+                                  ctypes.c_void_p, ctypes.c_double)
+        for name, scal in (("ref_gemm_f32", f32), ("ref_gemm_f16", f32), ("ref_gemm_i8", i32)):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_int, i64, i64, i64, scal, vp, i64, vp, i64, scal, vp, i64, vp, i64]
+        lib.ref_gemm_sample.restype = ctypes.c_int
+        lib.ref_gemm_sample.argtypes = [ctypes.c_int, ctypes.c_int, i64, dbl, vp, i64, vp, i64,
+                                        dbl, vp, i64, i64, vp, vp, vp]
+        lib.ref_half_to_double.restype = dbl
+        lib.ref_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.ref_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads():
+    """Threads the oracle's OpenMP loops use (OMP_NUM_THREADS or the core count)."""
+    return int(_load().ref_num_threads())
+
+
+def half_to_double(bits):
+    return float(_load().ref_half_to_double(int(bits) & 0xFFFF))
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _extent(layout, rows, cols, ld):
+    """Elements the buffer of a rows x cols matrix with leading dimension ld must hold."""
+    if rows == 0 or cols == 0:
+        return 0
+    return (cols - 1) * ld + rows if layout == "col" else (rows - 1) * ld + cols
+
+
+def _check(name, a, dtype, layout, rows, cols, ld):
+    if a is None:
+        return
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise ValueError("%s must be a C-contiguous %s buffer" % (name, np.dtype(dtype)))
+    if a.size < _extent(layout, rows, cols, ld):
+        raise ValueError("%s buffer too small for %dx%d with ld=%d" % (name, rows, cols, ld))
+
+
+def _run(fn, in_dtype, c_dtype, d_dtype, layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
+    _check("A", A, in_dtype, layout, M, K, lda)
+    _check("B", B, in_dtype, layout, K, N, ldb)
+    _check("C", C, c_dtype, layout, M, N, ldc)
+    ldd = max(1, M if layout == "col" else N)
+    D = np.zeros((N, M) if layout == "col" else (M, N), dtype=d_dtype)
+    if C is None:
+        if beta != 0:
+            raise ValueError("beta != 0 needs C")
+        ldc = ldd
+    rc = fn(_LAYOUT[layout], M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc, _ptr(D), ldd)
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    # D is returned as an M x N array (logical indexing), whatever the layout
+    return D.T if layout == "col" else D
+
+
+def gemm_f32(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
+    """float32 inputs; returns the un-narrowed double result as an (M, N) array."""
+    return _run(_load().ref_gemm_f32, np.float32, np.float32, np.float64,
+                layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+
+
+def gemm_f16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
+    """binary16 bit patterns (uint16) in, float32 C in; returns double (M, N)."""
+    return _run(_load().ref_gemm_f16, np.uint16, np.float32, np.float64,
+                layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+
+
+def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
+    """int8 inputs, int32 C in; returns the exact int64 result (M, N)."""
+    return _run(_load().ref_gemm_i8, np.int8, np.int32, np.int64,
+                layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+
+
+def gemm_sample(dtype, layout, K, alpha, A, lda, B, ldb, beta, C, ldc, rows, cols):
+    """The definition evaluated at positions (rows[s], cols[s]) only; returns double[nsamp]."""
+    code = {"f32": 0, "f16": 1, "i8": 2}[dtype]
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    cols = np.ascontiguousarray(cols, dtype=np.int64)
+    out = np.zeros(rows.size, dtype=np.float64)
+    if C is None and beta != 0:
+        raise ValueError("beta != 0 needs C")
+    rc = _load().ref_gemm_sample(code, _LAYOUT[layout], K, float(alpha), _ptr(A), lda, _ptr(B), ldb,
+                                 float(beta), _ptr(C), ldc, rows.size, _ptr(rows), _ptr(cols), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    return out
+
+
+def wrap_int32(d):
+    """Reduce exact int64 values modulo 2^32 into int32 (two's complement)."""
+    return np.asarray(d, dtype=np.int64).astype(np.uint64).astype(np.uint32).view(np.int32).reshape(np.shape(d))
+
+
+def normalised_error(c, c_ref, K, max_a, max_b):
+    """max |c - c_ref| / (K * max|A| * max|B|), the acceptance metric for floating point."""
+    c = np.asarray(c, dtype=np.float64)
+    c_ref = np.asarray(c_ref, dtype=np.float64)
+    if c.size == 0:
+        return 0.0
+    denom = float(K) * float(max_a) * float(max_b)
+    diff = float(np.max(np.abs(c - c_ref)))
+    if not np.all(np.isfinite(c)):
+        return float("inf")
+    return diff / denom if denom > 0 else (0.0 if diff == 0 else float("inf"))

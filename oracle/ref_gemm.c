@@ -1,0 +1,191 @@
+/*
+ * CPU oracle for C = alpha*A*B + beta*C.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the checker the GPU library is compared against.  It shares no
+ * code with the GPU path and must never be called from it: only the tests, the
+ * smoke check and the benchmark's CPU-baseline leg may load it.
+ *
+ * What it computes is the plain definition of the product (paper Sec. II-A:
+ * A is m x k, B is k x n, C is m x n) in the alpha/beta form of the paper's
+ * reference micro-kernel (Fig. "Exo code for GEMM micro-kernel"): every
+ * C(i,j) is a sum over p of A(i,p)*B(p,j), scaled by alpha, plus beta times
+ * the old C(i,j).  Blocking, packing and the micro-kernel of the paper only
+ * reorder that sum, so the definition itself is the oracle.
+ *
+ * Arithmetic: every product and the running sum are held in double (fp32 and
+ * binary16 inputs convert to double exactly, and a product of two of them is
+ * exact in double) or in int64 (int8 inputs).  alpha and beta are applied in
+ * the wide type.  beta == 0 means the old C is not read at all, so NaN or Inf
+ * stored there cannot leak into the result (reference-BLAS convention).
+ *
+ * All pointers are host pointers.  layout: 0 = column-major, X(i,j) at
+ * X[i + j*ldx]; 1 = row-major, X(i,j) at X[i*ldx + j].  The result goes to a
+ * separate wide buffer D with its own leading dimension ldd in the same layout.
+ * Return value: 0, or -1 for an unknown layout.
+ *
+ * Pins (tests/test_oracle_pins.py): exact rational brute force on 7x5x3,
+ * identity and permutation operands, all-ones and rank-1 closed forms,
+ * small-integer exactness, int8 extremes, all 65536 binary16 patterns against
+ * numpy's float16, and torch.matmul in float64/int64 on random inputs.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static inline size_t at(int layout, int64_t i, int64_t j, int64_t ld)
+{
+    return layout == 0 ? (size_t)i + (size_t)j * (size_t)ld
+                       : (size_t)i * (size_t)ld + (size_t)j;
+}
+
+/* IEEE 754 binary16 bit pattern -> double, exactly (1 sign, 5 exponent, 10 fraction bits). */
+double ref_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double v;
+    if (e == 0) {
+        v = (double)f * (1.0 / 16777216.0);            /* subnormal: f * 2^-24 */
+    } else if (e == 31) {
+        if (f == 0) {
+            v = 1.0 / 0.0;
+        } else {
+            v = 0.0 / 0.0;
+        }
+    } else {
+        double scale = 1.0;
+        int s = e - 25;                                 /* (1024+f) * 2^(e-25) */
+        while (s > 0) { scale *= 2.0; --s; }
+        while (s < 0) { scale *= 0.5; ++s; }
+        v = (double)(1024 + f) * scale;
+    }
+    return sign ? -v : v;
+}
+
+int ref_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* fp32 inputs, double accumulation, double result. */
+int ref_gemm_f32(int layout, int64_t M, int64_t N, int64_t K,
+                 float alpha, const float *A, int64_t lda,
+                 const float *B, int64_t ldb,
+                 float beta, const float *C, int64_t ldc,
+                 double *D, int64_t ldd)
+{
+    if (layout != 0 && layout != 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        for (int64_t i = 0; i < M; ++i) {
+            double acc = 0.0;
+            for (int64_t p = 0; p < K; ++p)
+                acc += (double)A[at(layout, i, p, lda)] * (double)B[at(layout, p, j, ldb)];
+            double r = (double)alpha * acc;
+            if (beta != 0.0f) r += (double)beta * (double)C[at(layout, i, j, ldc)];
+            D[at(layout, i, j, ldd)] = r;
+        }
+    }
+    return 0;
+}
+
+/* binary16 inputs (bit patterns), double accumulation, fp32 C in, double result. */
+int ref_gemm_f16(int layout, int64_t M, int64_t N, int64_t K,
+                 float alpha, const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb,
+                 float beta, const float *C, int64_t ldc,
+                 double *D, int64_t ldd)
+{
+    if (layout != 0 && layout != 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        for (int64_t i = 0; i < M; ++i) {
+            double acc = 0.0;
+            for (int64_t p = 0; p < K; ++p)
+                acc += ref_half_to_double(A[at(layout, i, p, lda)]) *
+                       ref_half_to_double(B[at(layout, p, j, ldb)]);
+            double r = (double)alpha * acc;
+            if (beta != 0.0f) r += (double)beta * (double)C[at(layout, i, j, ldc)];
+            D[at(layout, i, j, ldd)] = r;
+        }
+    }
+    return 0;
+}
+
+/* int8 inputs, int64 accumulation; D holds the exact int64 value of
+ * alpha*sum + beta*C (the caller wraps it to int32 where it wants to). */
+int ref_gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
+                int32_t alpha, const int8_t *A, int64_t lda,
+                const int8_t *B, int64_t ldb,
+                int32_t beta, const int32_t *C, int64_t ldc,
+                int64_t *D, int64_t ldd)
+{
+    if (layout != 0 && layout != 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        for (int64_t i = 0; i < M; ++i) {
+            int64_t acc = 0;
+            for (int64_t p = 0; p < K; ++p)
+                acc += (int64_t)A[at(layout, i, p, lda)] * (int64_t)B[at(layout, p, j, ldb)];
+            int64_t r = (int64_t)alpha * acc;
+            if (beta != 0) r += (int64_t)beta * (int64_t)C[at(layout, i, j, ldc)];
+            D[at(layout, i, j, ldd)] = r;
+        }
+    }
+    return 0;
+}
+
+/*
+ * The same definition evaluated only at listed positions (is[s], js[s]), for
+ * sizes where the full triple loop would take hours: out[s] = the wide value
+ * of C(is[s], js[s]).  dtype: 0 = fp32, 1 = binary16, 2 = int8 (out then holds
+ * the int64 result converted to double, exact below 2^53).
+ */
+int ref_gemm_sample(int dtype, int layout, int64_t K,
+                    double alpha, const void *A, int64_t lda,
+                    const void *B, int64_t ldb,
+                    double beta, const void *C, int64_t ldc,
+                    int64_t nsamp, const int64_t *is, const int64_t *js, double *out)
+{
+    if (layout != 0 && layout != 1) return -1;
+    if (dtype < 0 || dtype > 2) return -2;
+#pragma omp parallel for schedule(static)
+    for (int64_t s = 0; s < nsamp; ++s) {
+        int64_t i = is[s], j = js[s];
+        double r;
+        if (dtype == 2) {
+            const int8_t *a = (const int8_t *)A, *b = (const int8_t *)B;
+            int64_t acc = 0;
+            for (int64_t p = 0; p < K; ++p)
+                acc += (int64_t)a[at(layout, i, p, lda)] * (int64_t)b[at(layout, p, j, ldb)];
+            int64_t v = (int64_t)alpha * acc;
+            if (beta != 0.0) v += (int64_t)beta * (int64_t)((const int32_t *)C)[at(layout, i, j, ldc)];
+            r = (double)v;
+        } else {
+            double acc = 0.0;
+            if (dtype == 0) {
+                const float *a = (const float *)A, *b = (const float *)B;
+                for (int64_t p = 0; p < K; ++p)
+                    acc += (double)a[at(layout, i, p, lda)] * (double)b[at(layout, p, j, ldb)];
+            } else {
+                const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+                for (int64_t p = 0; p < K; ++p)
+                    acc += ref_half_to_double(a[at(layout, i, p, lda)]) *
+                           ref_half_to_double(b[at(layout, p, j, ldb)]);
+            }
+            r = alpha * acc;
+            if (beta != 0.0) r += beta * (double)((const float *)C)[at(layout, i, j, ldc)];
+        }
+        out[s] = r;
+    }
+    return 0;
+}

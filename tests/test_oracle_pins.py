@@ -1,0 +1,353 @@
+"""Pins for the CPU oracle: each test fixes it to something other than itself.
+
+The product has a closed definition (paper Sec. II-A, and the alpha/beta form
+of its reference micro-kernel), so the pins are: exact rational brute force on
+a tiny case, identity / permutation operands, closed forms (all-ones, rank-1),
+exact small-integer arithmetic in Python ints, int8 extremes, numpy's float16
+for every binary16 pattern, torch.matmul in float64 / int64, and algebraic
+invariants (K-split, zero padding, linearity in alpha, layout transposition).
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+LAYOUTS = ["col", "row"]
+
+
+def _get(layout, buf, i, j, ld):
+    flat = buf.reshape(-1)
+    return flat[i + j * ld] if layout == "col" else flat[i * ld + j]
+
+
+# ---------------------------------------------------------------- brute force
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_f32_7x5x3_exact_rational(layout):
+    """7x5x3 with padded leading dimensions against a sum written out in exact rationals."""
+    M, N, K = 7, 5, 3
+    pad = 2
+    lda = wl.tight_ld(layout, M, K) + pad
+    ldb = wl.tight_ld(layout, K, N) + pad + 1
+    ldc = wl.tight_ld(layout, M, N) + pad + 2
+    A = wl.uniform_f32(11, layout, M, K, lda)
+    B = wl.uniform_f32(12, layout, K, N, ldb)
+    C = wl.uniform_f32(13, layout, M, N, ldc)
+    alpha, beta = np.float32(1.5), np.float32(-0.75)
+    D = oracle.gemm_f32(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+    assert D.shape == (M, N)
+    for i in range(M):
+        for j in range(N):
+            s = Fraction(0)
+            for p in range(K):
+                s += Fraction(float(_get(layout, A, i, p, lda))) * Fraction(float(_get(layout, B, p, j, ldb)))
+            want = Fraction(float(alpha)) * s + Fraction(float(beta)) * Fraction(float(_get(layout, C, i, j, ldc)))
+            # fp64 evaluation of a 3-term sum of exact products: a few ulps of the magnitude
+            assert abs(Fraction(float(D[i, j])) - want) <= Fraction(1, 2 ** 48)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_i8_small_exact_python_ints(layout):
+    M, N, K = 6, 4, 9
+    lda = wl.tight_ld(layout, M, K) + 3
+    ldb = wl.tight_ld(layout, K, N) + 1
+    ldc = wl.tight_ld(layout, M, N) + 2
+    A = wl.uniform_i8(21, layout, M, K, lda)
+    B = wl.uniform_i8(22, layout, K, N, ldb)
+    C = wl.uniform_i32(23, layout, M, N, ldc)
+    alpha, beta = 3, -2
+    D = oracle.gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+    for i in range(M):
+        for j in range(N):
+            s = sum(int(_get(layout, A, i, p, lda)) * int(_get(layout, B, p, j, ldb)) for p in range(K))
+            assert int(D[i, j]) == alpha * s + beta * int(_get(layout, C, i, j, ldc))
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_f16_small_exact_rational(layout):
+    M, N, K = 5, 6, 4
+    lda = wl.tight_ld(layout, M, K) + 1
+    ldb = wl.tight_ld(layout, K, N) + 2
+    A = wl.normal_f16_bits(31, layout, M, K, lda)
+    B = wl.normal_f16_bits(32, layout, K, N, ldb)
+    D = oracle.gemm_f16(layout, M, N, K, 1.0, A, lda, B, ldb, 0.0, None, 0)
+    Af, Bf = A.view(np.float16), B.view(np.float16)
+    for i in range(M):
+        for j in range(N):
+            s = Fraction(0)
+            for p in range(K):
+                s += Fraction(float(_get(layout, Af, i, p, lda))) * Fraction(float(_get(layout, Bf, p, j, ldb)))
+            # binary16 products have 22-bit significands; a 4-term sum of them is exact in fp64
+            assert Fraction(float(D[i, j])) == s
+
+
+# ---------------------------------------------------------------- binary16 decode
+def test_half_decode_all_patterns():
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(b) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+# ---------------------------------------------------------------- identity / permutation
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_identity_and_permutation_f32(layout):
+    n, N = 13, 9
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(n)
+    P = np.zeros((n, n), dtype=np.float32)
+    P[np.arange(n), perm] = 1.0                      # (P @ B)[i] = B[perm[i]]
+    Bl = rng.standard_normal((n, N)).astype(np.float32)
+    Cl = rng.standard_normal((n, N)).astype(np.float32)
+
+    def buf(x):
+        return np.ascontiguousarray(x.T if layout == "col" else x)
+
+    lda, ldb, ldc = wl.tight_ld(layout, n, n), wl.tight_ld(layout, n, N), wl.tight_ld(layout, n, N)
+    eye = np.eye(n, dtype=np.float32)
+    D = oracle.gemm_f32(layout, n, N, n, 2.0, buf(eye), lda, buf(Bl), ldb, 0.5, buf(Cl), ldc)
+    assert np.array_equal(D, 2.0 * Bl.astype(np.float64) + 0.5 * Cl.astype(np.float64))
+    D = oracle.gemm_f32(layout, n, N, n, 1.0, buf(P), lda, buf(Bl), ldb, 0.0, None, 0)
+    assert np.array_equal(D, Bl[perm].astype(np.float64))
+    # identity on the right: C = A * I
+    Al = rng.standard_normal((N, n)).astype(np.float32)
+    D = oracle.gemm_f32(layout, N, n, n, 1.0, buf(Al), wl.tight_ld(layout, N, n), buf(eye), lda, 0.0, None, 0)
+    assert np.array_equal(D, Al.astype(np.float64))
+    # a column permutation from the right: (A @ P)[:, perm[i]] = A[:, i]
+    D = oracle.gemm_f32(layout, N, n, n, 1.0, buf(Al), wl.tight_ld(layout, N, n), buf(P), lda, 0.0, None, 0)
+    want = np.zeros((N, n))
+    want[:, perm] = Al
+    assert np.array_equal(D, want)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_permutation_i8_and_f16(layout):
+    n, N = 11, 7
+    rng = np.random.default_rng(6)
+    perm = rng.permutation(n)
+    P = np.zeros((n, n))
+    P[np.arange(n), perm] = 1
+
+    def buf(x, dt):
+        return np.ascontiguousarray((x.T if layout == "col" else x).astype(dt))
+
+    Bl = rng.integers(-128, 128, size=(n, N))
+    D = oracle.gemm_i8(layout, n, N, n, 1, buf(P, np.int8), wl.tight_ld(layout, n, n), buf(Bl, np.int8),
+                       wl.tight_ld(layout, n, N), 0, None, 0)
+    assert np.array_equal(D, Bl[perm])
+    Bh = rng.standard_normal((n, N)).astype(np.float16)
+    D = oracle.gemm_f16(layout, n, N, n, 1.0, buf(P, np.float16).view(np.uint16), wl.tight_ld(layout, n, n),
+                        buf(Bh, np.float16).view(np.uint16), wl.tight_ld(layout, n, N), 0.0, None, 0)
+    assert np.array_equal(D, Bh[perm].astype(np.float64))
+
+
+# ---------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("K", [1, 2, 63, 1000])
+def test_all_ones_and_rank1(layout, K):
+    M, N = 10, 12
+    ones_a = np.ones(wl._shape(layout, M, K, wl.tight_ld(layout, M, K)), dtype=np.float32)
+    ones_b = np.ones(wl._shape(layout, K, N, wl.tight_ld(layout, K, N)), dtype=np.float32)
+    D = oracle.gemm_f32(layout, M, N, K, 1.0, ones_a, wl.tight_ld(layout, M, K), ones_b,
+                        wl.tight_ld(layout, K, N), 0.0, None, 0)
+    assert np.all(D == K)
+    D = oracle.gemm_i8(layout, M, N, K, 1, ones_a.astype(np.int8), wl.tight_ld(layout, M, K),
+                       ones_b.astype(np.int8), wl.tight_ld(layout, K, N), 0, None, 0)
+    assert np.all(D == K)
+    D = oracle.gemm_f16(layout, M, N, K, 1.0, ones_a.astype(np.float16).view(np.uint16),
+                        wl.tight_ld(layout, M, K), ones_b.astype(np.float16).view(np.uint16),
+                        wl.tight_ld(layout, K, N), 0.0, None, 0)
+    assert np.all(D == K)
+    # rank-1: A(i,p) = i%7-3, B(p,j) = j%5-2  =>  C(i,j) = K * a_i * b_j
+    a = (np.arange(M) % 7 - 3).astype(np.float32)
+    b = (np.arange(N) % 5 - 2).astype(np.float32)
+    Al = np.repeat(a[:, None], K, axis=1)
+    Bl = np.repeat(b[None, :], K, axis=0)
+
+    def buf(x):
+        return np.ascontiguousarray(x.T if layout == "col" else x)
+
+    D = oracle.gemm_f32(layout, M, N, K, 1.0, buf(Al), wl.tight_ld(layout, M, K), buf(Bl),
+                        wl.tight_ld(layout, K, N), 0.0, None, 0)
+    assert np.array_equal(D, K * np.outer(a, b).astype(np.float64))
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_i8_extremes(layout):
+    M, N, K = 5, 4, 300
+
+    def full(rows, cols, v):
+        return np.full(wl._shape(layout, rows, cols, wl.tight_ld(layout, rows, cols)), v, dtype=np.int8)
+
+    lda, ldb = wl.tight_ld(layout, M, K), wl.tight_ld(layout, K, N)
+    D = oracle.gemm_i8(layout, M, N, K, 1, full(M, K, -128), lda, full(K, N, -128), ldb, 0, None, 0)
+    assert np.all(D == 16384 * K)
+    D = oracle.gemm_i8(layout, M, N, K, 1, full(M, K, -128), lda, full(K, N, 127), ldb, 0, None, 0)
+    assert np.all(D == -16256 * K)
+    D = oracle.gemm_i8(layout, M, N, K, 1, full(M, K, 127), lda, full(K, N, -128), ldb, 0, None, 0)
+    assert np.all(D == -16256 * K)
+
+
+def test_wrap_int32():
+    v = np.array([0, 1, -1, 2 ** 31 - 1, 2 ** 31, -2 ** 31, -2 ** 31 - 1, 2 ** 32 + 5, -2 ** 32 - 7], dtype=np.int64)
+    want = [((int(x) + 2 ** 31) % 2 ** 32) - 2 ** 31 for x in v]
+    assert oracle.wrap_int32(v).tolist() == want
+
+
+# ---------------------------------------------------------------- small integers: exact in any order
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (2.0, -1.0), (0.5, 1.0), (-1.0, 2.0)])
+def test_small_integer_inputs_exact(layout, alpha, beta):
+    M, N, K = 17, 9, 130
+    lda, ldb, ldc = wl.tight_ld(layout, M, K), wl.tight_ld(layout, K, N), wl.tight_ld(layout, M, N)
+    A = wl.small_int_f32(41, layout, M, K)
+    B = wl.small_int_f32(42, layout, K, N)
+    C = wl.small_int_f32(43, layout, M, N)
+    D = oracle.gemm_f32(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+    Ai = wl.logical(layout, A, M, K).astype(np.int64)
+    Bi = wl.logical(layout, B, K, N).astype(np.int64)
+    Ci = wl.logical(layout, C, M, N).astype(np.int64)
+    want2 = int(2 * alpha) * (Ai @ Bi) + int(2 * beta) * Ci       # doubled, to keep 0.5 integral
+    assert np.array_equal(2 * D, want2.astype(np.float64))
+    Dh = oracle.gemm_f16(layout, M, N, K, alpha, A.astype(np.float16).view(np.uint16), lda,
+                         B.astype(np.float16).view(np.uint16), ldb, beta, C, ldc)
+    assert np.array_equal(Dh, D)
+
+
+# ---------------------------------------------------------------- library second opinion
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape", [(64, 48, 200), (1, 1, 1), (33, 17, 129), (128, 3, 7)])
+def test_against_torch_matmul(layout, shape):
+    M, N, K = shape
+    lda = wl.tight_ld(layout, M, K) + 3
+    ldb = wl.tight_ld(layout, K, N) + 5
+    ldc = wl.tight_ld(layout, M, N) + 1
+    A = wl.uniform_f32(51, layout, M, K, lda)
+    B = wl.uniform_f32(52, layout, K, N, ldb)
+    C = wl.uniform_f32(53, layout, M, N, ldc)
+    alpha, beta = np.float32(1.5), np.float32(0.5)
+    D = oracle.gemm_f32(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+    tA = torch.from_numpy(wl.logical(layout, A, M, K).astype(np.float64))
+    tB = torch.from_numpy(wl.logical(layout, B, K, N).astype(np.float64))
+    tC = torch.from_numpy(wl.logical(layout, C, M, N).astype(np.float64))
+    want = (float(alpha) * (tA @ tB) + float(beta) * tC).numpy()
+    assert np.max(np.abs(D - want)) <= (K + 2) * 2.0 ** -52 * K      # |terms| <= 1
+    # binary16
+    Ah = wl.normal_f16_bits(54, layout, M, K, lda)
+    Bh = wl.normal_f16_bits(55, layout, K, N, ldb)
+    D = oracle.gemm_f16(layout, M, N, K, alpha, Ah, lda, Bh, ldb, beta, C, ldc)
+    tA = torch.from_numpy(wl.logical(layout, Ah.view(np.float16), M, K).astype(np.float64))
+    tB = torch.from_numpy(wl.logical(layout, Bh.view(np.float16), K, N).astype(np.float64))
+    want = (float(alpha) * (tA @ tB) + float(beta) * tC).numpy()
+    scale = float(tA.abs().max() * tB.abs().max()) if K else 0.0
+    assert np.max(np.abs(D - want)) <= (K + 2) * 2.0 ** -52 * K * max(scale, 1.0) * 2
+    # int8
+    Ai = wl.uniform_i8(56, layout, M, K, lda)
+    Bi = wl.uniform_i8(57, layout, K, N, ldb)
+    Ci = wl.uniform_i32(58, layout, M, N, ldc)
+    D = oracle.gemm_i8(layout, M, N, K, 2, Ai, lda, Bi, ldb, -1, Ci, ldc)
+    tA = torch.from_numpy(wl.logical(layout, Ai, M, K).astype(np.int64))
+    tB = torch.from_numpy(wl.logical(layout, Bi, K, N).astype(np.int64))
+    tC = torch.from_numpy(wl.logical(layout, Ci, M, N).astype(np.int64))
+    assert np.array_equal(D, (2 * (tA @ tB) - tC).numpy())
+
+
+# ---------------------------------------------------------------- invariants
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_layout_transposition_identity(layout):
+    """A row-major call equals the column-major call on the same buffers with operands swapped."""
+    M, N, K = 9, 14, 21
+    other = "row" if layout == "col" else "col"
+    A = wl.uniform_f32(61, layout, M, K)
+    B = wl.uniform_f32(62, layout, K, N)
+    C = wl.uniform_f32(63, layout, M, N)
+    D = oracle.gemm_f32(layout, M, N, K, 1.25, A, wl.tight_ld(layout, M, K), B, wl.tight_ld(layout, K, N),
+                        -0.5, C, wl.tight_ld(layout, M, N))
+    # the same bytes read in the other layout hold A^T (K x M), B^T (N x K), C^T (N x M)
+    Dt = oracle.gemm_f32(other, N, M, K, 1.25, B, wl.tight_ld(other, N, K), A, wl.tight_ld(other, K, M),
+                         -0.5, C, wl.tight_ld(other, N, M))
+    assert np.array_equal(D, Dt.T)
+
+
+def test_k_split_zero_padding_and_linearity():
+    layout = "col"
+    M, N, K = 12, 10, 40
+    A = wl.small_int_f32(71, layout, M, K)
+    B = wl.small_int_f32(72, layout, K, N)
+    full = oracle.gemm_f32(layout, M, N, K, 1.0, A, M, B, K, 0.0, None, 0)
+    # K split: first 25 columns of A with first 25 rows of B, then the rest accumulated with beta = 1
+    K1 = 25
+    part = oracle.gemm_f32(layout, M, N, K1, 1.0, A, M, B, K, 0.0, None, 0)
+    part32 = np.ascontiguousarray(part.T.astype(np.float32))
+    rest = oracle.gemm_f32(layout, M, N, K - K1, 1.0, A.reshape(-1)[K1 * M:], M, B.reshape(-1)[K1:], K,
+                           1.0, part32, M)
+    assert np.array_equal(rest, full)
+    # zero padding of K changes nothing
+    Ap = np.zeros((K + 5, M), dtype=np.float32)
+    Ap[:K] = A
+    Bp = np.zeros((N, K + 5), dtype=np.float32)
+    Bp[:, :K] = B
+    padded = oracle.gemm_f32(layout, M, N, K + 5, 1.0, Ap, M, Bp, K + 5, 0.0, None, 0)
+    assert np.array_equal(padded, full)
+    # linearity in alpha (exact for powers of two)
+    assert np.array_equal(oracle.gemm_f32(layout, M, N, K, 4.0, A, M, B, K, 0.0, None, 0), 4.0 * full)
+
+
+def test_beta_zero_ignores_old_c_and_k_zero():
+    layout = "col"
+    M, N, K = 4, 3, 5
+    A = wl.uniform_f32(81, layout, M, K)
+    B = wl.uniform_f32(82, layout, K, N)
+    C = np.full((N, M), np.nan, dtype=np.float32)
+    D = oracle.gemm_f32(layout, M, N, K, 1.0, A, M, B, K, 0.0, C, M)
+    assert np.all(np.isfinite(D))
+    C = wl.uniform_f32(83, layout, M, N)
+    D = oracle.gemm_f32(layout, M, N, 0, 1.0, A, M, B, 1, 2.0, C, M)
+    assert np.array_equal(D, 2.0 * wl.logical(layout, C, M, N).astype(np.float64))
+
+
+# ---------------------------------------------------------------- sampled evaluation agrees with the full one
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_sampled_oracle_matches_full(layout):
+    M, N, K = 40, 30, 77
+    lda, ldb, ldc = wl.tight_ld(layout, M, K) + 1, wl.tight_ld(layout, K, N) + 2, wl.tight_ld(layout, M, N) + 3
+    rng = np.random.default_rng(9)
+    rows, cols = rng.integers(0, M, 50), rng.integers(0, N, 50)
+    A, B, C = wl.uniform_f32(91, layout, M, K, lda), wl.uniform_f32(92, layout, K, N, ldb), wl.uniform_f32(93, layout, M, N, ldc)
+    D = oracle.gemm_f32(layout, M, N, K, 1.5, A, lda, B, ldb, 0.5, C, ldc)
+    s = oracle.gemm_sample("f32", layout, K, 1.5, A, lda, B, ldb, 0.5, C, ldc, rows, cols)
+    assert np.array_equal(s, D[rows, cols])
+    Ah, Bh = wl.normal_f16_bits(94, layout, M, K, lda), wl.normal_f16_bits(95, layout, K, N, ldb)
+    D = oracle.gemm_f16(layout, M, N, K, 1.0, Ah, lda, Bh, ldb, 0.0, None, 0)
+    s = oracle.gemm_sample("f16", layout, K, 1.0, Ah, lda, Bh, ldb, 0.0, None, 0, rows, cols)
+    assert np.array_equal(s, D[rows, cols])
+    Ai, Bi, Ci = wl.uniform_i8(96, layout, M, K, lda), wl.uniform_i8(97, layout, K, N, ldb), wl.uniform_i32(98, layout, M, N, ldc)
+    D = oracle.gemm_i8(layout, M, N, K, 2, Ai, lda, Bi, ldb, -1, Ci, ldc)
+    s = oracle.gemm_sample("i8", layout, K, 2, Ai, lda, Bi, ldb, -1, Ci, ldc, rows, cols)
+    assert np.array_equal(s, D[rows, cols].astype(np.float64))
+
+
+# ---------------------------------------------------------------- the metric tells fp16 accumulation apart
+def test_metric_distinguishes_fp16_accumulation():
+    """A result accumulated in binary16 must fail a bound that fp32 accumulation passes easily."""
+    layout = "row"
+    M, N, K = 16, 16, 8192
+    A = wl.normal_f16_bits(101, layout, M, K)
+    B = wl.normal_f16_bits(102, layout, K, N)
+    D = oracle.gemm_f16(layout, M, N, K, 1.0, A, K, B, N, 0.0, None, 0)
+    Af, Bf = A.view(np.float16), B.view(np.float16)
+    max_a, max_b = float(np.abs(Af.astype(np.float64)).max()), float(np.abs(Bf.astype(np.float64)).max())
+    acc16 = np.zeros((M, N), dtype=np.float16)
+    acc32 = np.zeros((M, N), dtype=np.float32)
+    for p in range(K):
+        prod = np.outer(Af[:, p].astype(np.float32), Bf[p, :].astype(np.float32))     # exact in fp32
+        acc16 = (acc16.astype(np.float32) + prod).astype(np.float16)
+        acc32 = acc32 + prod
+    assert oracle.normalised_error(acc32, D, K, max_a, max_b) < 1e-7
+    assert oracle.normalised_error(acc16, D, K, max_a, max_b) > 1e-5
