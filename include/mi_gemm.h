@@ -1,0 +1,117 @@
+/*
+ * mi_gemm - general matrix multiplication C = alpha*A*B + beta*C on one MI355X.
+ *
+ * The operation is the GEMM of the paper's Sec. II-A (A is M x K, B is K x N,
+ * C is M x N) in the alpha/beta form of its reference micro-kernel (Fig. "Exo
+ * code for GEMM micro-kernel").  The implementation follows the structure of
+ * the paper's Fig. "Pseudo-code of the BLIS base GEMM algorithm" re-mapped to
+ * the GPU: loops L1 and L3 become the grid of workgroup tiles, loop L2 becomes
+ * the K loop of a workgroup (optionally split over workgroups), the packing
+ * routines become the staging of operand tiles into LDS, loops L4/L5 become the
+ * waves of a workgroup and their MFMA blocks, and the micro-kernel (L6) is a
+ * chain of MFMA instructions on accumulators held in registers.
+ *
+ * Common conventions for the three entry points
+ * ---------------------------------------------
+ * layout   MI_GEMM_COL_MAJOR: X(i,j) is X[i + j*ldx];  MI_GEMM_ROW_MAJOR:
+ *          X(i,j) is X[i*ldx + j].  One layout applies to A, B and C.  There
+ *          are no transpose flags.
+ * M, N, K  >= 0.  M == 0 or N == 0: nothing is touched.  K == 0 or alpha == 0:
+ *          C <- beta*C and A, B are never read.
+ * A, B, C  DEVICE pointers owned by the caller; A and B are only read, C is
+ *          read (unless beta == 0) and written.  beta == 0 means C is
+ *          overwritten and its old contents - NaN and Inf included - are never
+ *          read.  C must not overlap A, B or the workspace.  Only natural
+ *          element alignment is required; 16-byte aligned base pointers and
+ *          leading dimensions that are multiples of 16 bytes select the fast
+ *          loaders.
+ * lda/b/c  leading dimensions in elements: column-major lda >= max(1,M),
+ *          ldb >= max(1,K), ldc >= max(1,M); row-major lda >= max(1,K),
+ *          ldb >= max(1,N), ldc >= max(1,N).
+ * workspace, workspace_bytes
+ *          optional DEVICE scratch owned by the caller, used when the K loop
+ *          is split over several workgroups (few output tiles, long K).  It
+ *          may be NULL / 0: the library then runs without splitting.  The
+ *          library itself never allocates device memory.  A size of at least
+ *          gemm_workspace_bytes(...) allows every split the selector may pick.
+ *          The base must be 16-byte aligned.
+ * stream   a hipStream_t passed as void*; NULL is the default stream.  Calls
+ *          are asynchronous on that stream; the library never synchronises.
+ *
+ * Return value: 0 on success; -k if the k-th argument (1-based, in the order
+ * of the prototype) is illegal, in which case nothing was launched; a positive
+ * value is a HIP error code from the launch.  gemm_status_string() describes
+ * any of them.
+ *
+ * Results are deterministic: the same call on the same data gives the same
+ * bits, whatever the workspace size (a split K loop is reduced in fixed order).
+ */
+#ifndef MI_GEMM_H
+#define MI_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MI_GEMM_COL_MAJOR = 0, MI_GEMM_ROW_MAJOR = 1 };
+enum { MI_GEMM_F32 = 0, MI_GEMM_F16 = 1, MI_GEMM_I8 = 2 };
+
+/* fp32 inputs and output, true fp32 MFMA arithmetic (no reduced-precision
+ * splitting), fp32 accumulation.  Paper Sec. II-A; alpha/beta as in its
+ * reference micro-kernel. */
+int gemm_f32(int layout, int64_t M, int64_t N, int64_t K,
+             float alpha, const float *A, int64_t lda,
+             const float *B, int64_t ldb,
+             float beta, float *C, int64_t ldc,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+/* IEEE binary16 inputs (bit patterns), fp32 accumulation, fp32 C in and out.
+ * The data-type retargeting of the paper's Sec. "Data types". */
+int gemm_f16(int layout, int64_t M, int64_t N, int64_t K,
+             float alpha, const uint16_t *A, int64_t lda,
+             const uint16_t *B, int64_t ldb,
+             float beta, float *C, int64_t ldc,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+/* int8 inputs, int32 accumulation, int32 C in and out, int32 alpha and beta.
+ * The result is exact (bit-for-bit) as long as the true value of every
+ * intermediate fits in int32, which holds for K <= 131071 at alpha = 1,
+ * beta = 0; beyond that the arithmetic wraps modulo 2^32. */
+int gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
+            int32_t alpha, const int8_t *A, int64_t lda,
+            const int8_t *B, int64_t ldb,
+            int32_t beta, int32_t *C, int64_t ldc,
+            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Upper bound of the workspace any split of the K loop may use for this
+ * problem (dtype is one of MI_GEMM_F32/F16/I8); 0 if M, N or K is not positive. */
+size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K);
+
+/* Text for a status returned by the entry points (static storage). */
+const char *gemm_status_string(int status);
+
+/*
+ * Kernel table introspection, for tests, tuning and reports.  Each dtype has
+ * gemm_kernel_count(dtype) tile configurations ("per-shape micro-kernels" in
+ * the paper's terms, Sec. "Edge Cases"), numbered from 0.
+ * gemm_kernel_name() returns a static string such as "f32_128x128_w64x64".
+ * gemm_force_kernel(dtype, id, split) overrides the selector for later calls
+ * of this process: id = -1 restores automatic selection; split <= 0 lets the
+ * selector choose the K split, split >= 1 fixes it (clamped to what the
+ * workspace allows).  Returns 0, or -1 for an unknown dtype / id.
+ * gemm_last_kernel_id() / gemm_last_split() report what the most recent call
+ * on this thread launched (-1 / 0 if it launched no MFMA kernel).
+ */
+int gemm_kernel_count(int dtype);
+const char *gemm_kernel_name(int dtype, int id);
+int gemm_force_kernel(int dtype, int id, int split);
+int gemm_last_kernel_id(void);
+int gemm_last_split(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI_GEMM_H */

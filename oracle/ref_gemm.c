@@ -31,6 +31,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string.h>
+#include <math.h>
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -58,11 +59,7 @@ double ref_half_to_double(uint16_t h)
             v = 0.0 / 0.0;
         }
     } else {
-        double scale = 1.0;
-        int s = e - 25;                                 /* (1024+f) * 2^(e-25) */
-        while (s > 0) { scale *= 2.0; --s; }
-        while (s < 0) { scale *= 0.5; ++s; }
-        v = (double)(1024 + f) * scale;
+        v = ldexp((double)(1024 + f), e - 25);          /* (1024+f) * 2^(e-25) */
     }
     return sign ? -v : v;
 }

@@ -1,0 +1,131 @@
+"""ctypes binding of libmi_gemm.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point
+(include/mi_gemm.h).  Matrix arguments are torch tensors on the GPU (any shape;
+only data_ptr() is used) or raw integer device addresses; `stream` is a
+torch.cuda.Stream, a raw hipStream_t value or None for torch's current stream.
+`workspace` is a torch tensor (its byte size is taken from it) or None.
+Nothing here computes: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+COL_MAJOR, ROW_MAJOR = 0, 1
+F32, F16, I8 = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmi_gemm.so")
+_lib = None
+
+
+class GemmError(RuntimeError):
+    def __init__(self, status, text):
+        RuntimeError.__init__(self, "mi_gemm status %d: %s" % (status, text))
+        self.status = status
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load():
+    """Load the built library; build it first if it was never built (needs hipcc)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    for name, scal in (("gemm_f32", ctypes.c_float), ("gemm_f16", ctypes.c_float), ("gemm_i8", ctypes.c_int32)):
+        fn = getattr(lib, name)
+        fn.restype = ci
+        fn.argtypes = [ci, i64, i64, i64, scal, vp, i64, vp, i64, scal, vp, i64, vp, sz, vp]
+    lib.gemm_workspace_bytes.restype = sz
+    lib.gemm_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    lib.gemm_status_string.restype = ctypes.c_char_p
+    lib.gemm_status_string.argtypes = [ci]
+    lib.gemm_kernel_count.restype = ci
+    lib.gemm_kernel_count.argtypes = [ci]
+    lib.gemm_kernel_name.restype = ctypes.c_char_p
+    lib.gemm_kernel_name.argtypes = [ci, ci]
+    lib.gemm_force_kernel.restype = ci
+    lib.gemm_force_kernel.argtypes = [ci, ci, ci]
+    lib.gemm_last_kernel_id.restype = ci
+    lib.gemm_last_split.restype = ci
+    _lib = lib
+    return lib
+
+
+def _addr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def _call(name, layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check):
+    lib = load()
+    ws, ws_bytes = _ws(workspace)
+    status = getattr(lib, name)(layout, M, N, K, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C), ldc,
+                                ws, ws_bytes, _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, gemm_status_string(status))
+    return status
+
+
+def gemm_f32(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    return _call("gemm_f32", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def gemm_f16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    return _call("gemm_f16", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    return _call("gemm_i8", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def gemm_workspace_bytes(dtype, M, N, K):
+    return int(load().gemm_workspace_bytes(dtype, M, N, K))
+
+
+def gemm_status_string(status):
+    return load().gemm_status_string(status).decode()
+
+
+def gemm_kernel_count(dtype):
+    return int(load().gemm_kernel_count(dtype))
+
+
+def gemm_kernel_name(dtype, kernel_id):
+    return load().gemm_kernel_name(dtype, kernel_id).decode()
+
+
+def gemm_force_kernel(dtype, kernel_id=-1, split=0):
+    return int(load().gemm_force_kernel(dtype, kernel_id, split))
+
+
+def gemm_last_kernel_id():
+    return int(load().gemm_last_kernel_id())
+
+
+def gemm_last_split():
+    return int(load().gemm_last_split())

@@ -1,0 +1,245 @@
+// C-ABI entry points: argument checks, quick returns, layout canonicalisation,
+// tile selection and launch.  Host code only; the kernels live in
+// gemm_table.hip.  Declarations and the full contract are in include/mi_gemm.h.
+#include "../../include/mi_gemm.h"
+#include "gemm_table.h"
+
+#include <hip/hip_runtime_api.h>
+#include <limits.h>
+#include <stdio.h>
+#include <string.h>
+
+using namespace mig;
+
+namespace {
+
+constexpr int NUM_CU = 256;      // MI355X compute units
+constexpr int MAX_SPLIT = 32;    // upper limit of the K split
+
+struct Forced { int id = -1; int split = 0; };
+Forced g_forced[3];
+thread_local int t_last_id = -1;
+thread_local int t_last_split = 0;
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// What the selector settles on for one canonical problem.
+struct Choice { int id; int split; int ktiles_per_split; };
+
+// K split for a given tile: only when the grid would leave most CUs idle and K
+// is long enough to give every slice at least two steps.
+int auto_split(int64_t tiles, int64_t ktiles)
+{
+    if (tiles >= NUM_CU * 3 / 4 || ktiles < 4) return 1;
+    int64_t s = ceil_div(NUM_CU, tiles);
+    if (s > ktiles / 2) s = ktiles / 2;
+    if (s > MAX_SPLIT) s = MAX_SPLIT;
+    return s < 1 ? 1 : (int)s;
+}
+
+// Tile selection (the analogue of choosing the micro-kernel size that matches
+// the problem, paper Secs. "Edge Cases" and "Squared Matrices"): the largest
+// tile that still gives every CU a workgroup, else the smallest tile.
+int auto_kernel(int dtype, int64_t M, int64_t N)
+{
+    const int n = kernel_count(dtype);
+    int best = -1;
+    int64_t best_area = 0;
+    int smallest = 0;
+    int64_t smallest_area = INT64_MAX;
+    for (int id = 0; id < n; ++id) {
+        const KernelInfo *ki = kernel_info(dtype, id);
+        const int64_t area = (int64_t)ki->BM * ki->BN;
+        const int64_t tiles = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
+        if (area < smallest_area) { smallest_area = area; smallest = id; }
+        if (tiles >= NUM_CU && area > best_area) { best_area = area; best = id; }
+    }
+    if (dtype == MI_GEMM_F32 && best == 1) best = 0;   // 256x128 is opt-in until it is measured to win
+    return best >= 0 ? best : smallest;
+}
+
+Choice choose(int dtype, int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool have_ws)
+{
+    Choice c;
+    const Forced f = g_forced[dtype];
+    c.id = (f.id >= 0 && f.id < kernel_count(dtype)) ? f.id : auto_kernel(dtype, M, N);
+    const KernelInfo *ki = kernel_info(dtype, c.id);
+    const int64_t tiles = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
+    const int64_t ktiles = ceil_div(K, ki->BK);
+    int64_t s = f.split >= 1 ? f.split : auto_split(tiles, ktiles);
+    if (s > ktiles) s = ktiles;
+    if (s > MAX_SPLIT) s = MAX_SPLIT;
+    if (s > 1) {
+        const unsigned __int128 per = (unsigned __int128)M * (unsigned __int128)N * 4u;
+        const int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
+        if (s > fit) s = fit;
+    }
+    if (s < 1) s = 1;
+    c.ktiles_per_split = (int)ceil_div(ktiles, s);
+    c.split = (int)ceil_div(ktiles, c.ktiles_per_split);   // every slice gets at least one step
+    return c;
+}
+
+bool aligned16(const void *p, int64_t ld, int es)
+{
+    return ((uintptr_t)p % 16 == 0) && ((ld * es) % 16 == 0);
+}
+
+int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t alpha_bits, bool alpha_zero,
+        const void *A, int64_t lda, const void *B, int64_t ldb, uint32_t beta_bits, bool beta_zero, bool beta_one,
+        void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream_)
+{
+    t_last_id = -1;
+    t_last_split = 0;
+    if (layout != MI_GEMM_COL_MAJOR && layout != MI_GEMM_ROW_MAJOR) return -1;
+    if (M < 0 || M > INT_MAX) return -2;
+    if (N < 0 || N > INT_MAX) return -3;
+    if (K < 0 || K > INT_MAX) return -4;
+    const bool col = (layout == MI_GEMM_COL_MAJOR);
+    const int64_t one = 1;
+    if (lda < (col ? (M > one ? M : one) : (K > one ? K : one))) return -7;
+    if (ldb < (col ? (K > one ? K : one) : (N > one ? N : one))) return -9;
+    if (ldc < (col ? (M > one ? M : one) : (N > one ? N : one))) return -12;
+    if (ws != nullptr && (uintptr_t)ws % 16 != 0) return -13;
+    if (M == 0 || N == 0) return 0;
+    if (C == nullptr) return -11;
+    const bool no_product = (K == 0) || alpha_zero;
+    if (!no_product && A == nullptr) return -6;
+    if (!no_product && B == nullptr) return -8;
+
+    hipStream_t stream = (hipStream_t)stream_;
+
+    // canonical form: C' column-major M' x N'.  A row-major problem is the
+    // column-major problem C^T = B^T A^T on the same buffers.
+    int64_t Mc = M, Nc = N;
+    const void *Ac = A, *Bc = B;
+    int64_t ldac = lda, ldbc = ldb;
+    if (!col) {
+        Mc = N; Nc = M;
+        Ac = B; ldac = ldb;
+        Bc = A; ldbc = lda;
+    }
+
+    if (no_product) {
+        if (beta_one) return 0;
+        hipError_t e = launch_scale(dtype, C, (int)Mc, (int)Nc, ldc, beta_bits, beta_zero ? 0 : 1, stream);
+        return e == hipSuccess ? 0 : (int)e;
+    }
+
+    const Choice ch = choose(dtype, Mc, Nc, K, ws_bytes, ws != nullptr);
+    const KernelInfo *ki = kernel_info(dtype, ch.id);
+
+    Params p;
+    memset(&p, 0, sizeof(p));
+    p.A = Ac; p.B = Bc; p.C = C; p.ws = ws;
+    p.lda = ldac; p.ldb = ldbc; p.ldc = ldc;
+    p.M = (int)Mc; p.N = (int)Nc; p.K = (int)K;
+    p.tiles_m = (int)ceil_div(Mc, ki->BM);
+    p.tiles_n = (int)ceil_div(Nc, ki->BN);
+    if ((int64_t)p.tiles_m * p.tiles_n > INT_MAX) return -2;
+    p.ktiles = (int)ceil_div(K, ki->BK);
+    p.ktiles_per_split = ch.ktiles_per_split;
+    p.split = ch.split;
+    p.alpha_bits = alpha_bits;
+    p.beta_bits = beta_bits;
+    p.use_beta = beta_zero ? 0 : 1;
+    p.vecA = aligned16(Ac, ldac, es) ? 1 : 0;
+    p.vecB = aligned16(Bc, ldbc, es) ? 1 : 0;
+    p.group_m = 8;
+    p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
+
+    hipError_t e = ki->launch(p, stream);
+    if (e != hipSuccess) return (int)e;
+    if (p.split > 1) {
+        e = launch_reduce(dtype, ws, C, p.M, p.N, ldc, p.split, alpha_bits, beta_bits, p.use_beta, stream);
+        if (e != hipSuccess) return (int)e;
+    }
+    t_last_id = ch.id;
+    t_last_split = ch.split;
+    return 0;
+}
+
+uint32_t bits_of(float x) { uint32_t u; memcpy(&u, &x, 4); return u; }
+
+}  // namespace
+
+extern "C" {
+
+int gemm_f32(int layout, int64_t M, int64_t N, int64_t K, float alpha, const float *A, int64_t lda, const float *B,
+             int64_t ldb, float beta, float *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run(MI_GEMM_F32, 4, layout, M, N, K, bits_of(alpha), alpha == 0.0f, A, lda, B, ldb, bits_of(beta),
+               beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream);
+}
+
+int gemm_f16(int layout, int64_t M, int64_t N, int64_t K, float alpha, const uint16_t *A, int64_t lda,
+             const uint16_t *B, int64_t ldb, float beta, float *C, int64_t ldc, void *workspace,
+             size_t workspace_bytes, void *stream)
+{
+    return run(MI_GEMM_F16, 2, layout, M, N, K, bits_of(alpha), alpha == 0.0f, A, lda, B, ldb, bits_of(beta),
+               beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream);
+}
+
+int gemm_i8(int layout, int64_t M, int64_t N, int64_t K, int32_t alpha, const int8_t *A, int64_t lda, const int8_t *B,
+            int64_t ldb, int32_t beta, int32_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run(MI_GEMM_I8, 1, layout, M, N, K, (uint32_t)alpha, alpha == 0, A, lda, B, ldb, (uint32_t)beta, beta == 0,
+               beta == 1, C, ldc, workspace, workspace_bytes, stream);
+}
+
+size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
+{
+    if (dtype < 0 || dtype > 2 || M <= 0 || N <= 0 || K <= 0) return 0;
+    if (M > INT_MAX || N > INT_MAX || K > INT_MAX) return 0;
+    // the largest split any tile of this dtype would be given by the selector
+    int64_t smax = 1;
+    for (int id = 0; id < kernel_count(dtype); ++id) {
+        const KernelInfo *ki = kernel_info(dtype, id);
+        // either orientation: a row-major call runs the transposed problem
+        const int64_t t1 = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
+        const int64_t t2 = ceil_div(N, ki->BM) * ceil_div(M, ki->BN);
+        const int64_t s1 = auto_split(t1, ceil_div(K, ki->BK)), s2 = auto_split(t2, ceil_div(K, ki->BK));
+        if (s1 > smax) smax = s1;
+        if (s2 > smax) smax = s2;
+    }
+    if (smax <= 1) return 0;
+    return (size_t)smax * (size_t)M * (size_t)N * 4u;
+}
+
+const char *gemm_status_string(int status)
+{
+    static const char *const arg[] = {
+        "ok", "argument 1 (layout) is not MI_GEMM_COL_MAJOR or MI_GEMM_ROW_MAJOR",
+        "argument 2 (M) is negative or too large", "argument 3 (N) is negative or too large",
+        "argument 4 (K) is negative or too large", "argument 5 (alpha) is illegal", "argument 6 (A) is NULL",
+        "argument 7 (lda) is smaller than the extent of A's contiguous dimension", "argument 8 (B) is NULL",
+        "argument 9 (ldb) is smaller than the extent of B's contiguous dimension", "argument 10 (beta) is illegal",
+        "argument 11 (C) is NULL", "argument 12 (ldc) is smaller than the extent of C's contiguous dimension",
+        "argument 13 (workspace) is not 16-byte aligned", "argument 14 (workspace_bytes) is illegal",
+        "argument 15 (stream) is illegal"};
+    if (status <= 0 && status >= -15) return arg[-status];
+    if (status > 0) return hipGetErrorString((hipError_t)status);
+    return "unknown status";
+}
+
+int gemm_kernel_count(int dtype) { return (dtype >= 0 && dtype <= 2) ? kernel_count(dtype) : 0; }
+
+const char *gemm_kernel_name(int dtype, int id)
+{
+    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    return ki ? ki->name : "";
+}
+
+int gemm_force_kernel(int dtype, int id, int split)
+{
+    if (dtype < 0 || dtype > 2) return -1;
+    if (id < -1 || id >= kernel_count(dtype)) return -1;
+    g_forced[dtype].id = id;
+    g_forced[dtype].split = split > 0 ? split : 0;
+    return 0;
+}
+
+int gemm_last_kernel_id(void) { return t_last_id; }
+int gemm_last_split(void) { return t_last_split; }
+
+}  // extern "C"

@@ -1,0 +1,461 @@
+// Workgroup-tile GEMM kernel for gfx950 (MI355X): the macro-kernel and the
+// micro-kernel of the paper's Fig. "Pseudo-code of the BLIS base GEMM
+// algorithm", re-mapped to the GPU.
+//
+//   loops L1 (jc) and L3 (ic)  -> the grid: one workgroup per BM x BN tile of C
+//   loop  L2 (pc)              -> the K loop of a workgroup, in steps of BK
+//                                 (one 128-byte row segment per step), and,
+//                                 when asked for, split over blockIdx.y
+//   Pack A / Pack B            -> staging of the operand tiles into LDS, both
+//                                 stored row by row with K contiguous, so that
+//                                 the micro-kernel reads its operands with unit
+//                                 stride (the paper's reason for packing)
+//   loops L4 (jr) and L5 (ir)  -> the waves of the workgroup and the 32 x 32
+//                                 MFMA blocks of each wave tile
+//   micro-kernel L6            -> a chain of MFMA instructions that keeps the
+//                                 wave's block of C in registers over the whole
+//                                 K loop, as C_reg does in the paper's Sec.
+//                                 "Micro-kernel Generation"
+//
+// Canonical problem (the host swaps operands for row-major callers):
+//   C is M x N column-major, element (m,n) at C[m + n*ldc];
+//   A is M x K with M contiguous, element (m,k) at A[m + k*lda];
+//   B is K x N with K contiguous, element (k,n) at B[k + n*ldb].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "gemm_table.h"
+
+namespace mig {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+// ---------------------------------------------------------------- data types
+struct F32 {
+    typedef float elt;
+    typedef float acc_t;
+    typedef v16f accv;
+    static constexpr int ES = 4;    // bytes per input element
+    static constexpr int KCH = 4;   // K elements per 16-byte chunk
+};
+struct F16 {
+    typedef uint16_t elt;
+    typedef float acc_t;
+    typedef v16f accv;
+    static constexpr int ES = 2;
+    static constexpr int KCH = 8;
+};
+struct I8 {
+    typedef int8_t elt;
+    typedef int acc_t;
+    typedef v16i accv;
+    static constexpr int ES = 1;
+    static constexpr int KCH = 16;
+};
+
+// One 16-byte fragment per lane and operand feeds 4 (fp32), 1 (fp16) or
+// 1 (int8) MFMA instructions.  `rowop` is the operand whose tile rows become
+// the rows of the 32 x 32 result block (held in registers), `colop` the one
+// whose rows become its columns (one per lane).
+template <class DT> struct Mma;
+template <> struct Mma<F32> {
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v16f &c) {
+        v4f a = __builtin_bit_cast(v4f, rowop), b = __builtin_bit_cast(v4f, colop);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
+    }
+};
+template <> struct Mma<F16> {
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v16f &c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, rowop),
+                                                   __builtin_bit_cast(v8h, colop), c, 0, 0, 0);
+    }
+};
+template <> struct Mma<I8> {
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v16i &c) {
+        c = __builtin_amdgcn_mfma_i32_32x32x32_i8(rowop, colop, c, 0, 0, 0);
+    }
+};
+
+// ---------------------------------------------------------------- register transposes
+// The A operand arrives with M contiguous: a lane loads KCH vectors, one per k,
+// of MB consecutive m each, and turns them into MB chunks of KCH consecutive k.
+// raw[kk][w] is 32-bit word w of the vector loaded for k offset kk.
+template <class DT, int MB> struct Transpose;
+
+template <int MB> struct Transpose<F32, MB> {     // MB = 2 or 4
+    static __device__ __forceinline__ v4i chunk(const int (&raw)[4][MB], int c) {
+        v4i o;
+        o[0] = raw[0][c]; o[1] = raw[1][c]; o[2] = raw[2][c]; o[3] = raw[3][c];
+        return o;
+    }
+};
+
+template <int MB> struct Transpose<F16, MB> {     // MB = 2, 4 or 8
+    static __device__ __forceinline__ v4i chunk(const int (&raw)[8][MB / 2], int c) {
+        v4i o;
+#pragma unroll
+        for (int kp = 0; kp < 4; ++kp) {
+            uint32_t x = (uint32_t)raw[2 * kp][c >> 1], y = (uint32_t)raw[2 * kp + 1][c >> 1];
+            o[kp] = (c & 1) ? (int)((x >> 16) | (y & 0xffff0000u)) : (int)((x & 0xffffu) | (y << 16));
+        }
+        return o;
+    }
+};
+
+__device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+    return __builtin_amdgcn_perm(hi, lo, sel);   // bytes 0-3 index lo, 4-7 index hi
+}
+
+template <int MB> struct Transpose<I8, MB> {     // MB = 4 or 8
+    static constexpr int WORDS = MB / 4;
+    // all MB chunks at once: out[c] holds k = 0..15 of row c
+    static __device__ __forceinline__ void all(const int (&raw)[16][WORDS], v4i (&out)[MB]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int w = 0; w < WORDS; ++w) {
+                uint32_t r0 = raw[4 * q][w], r1 = raw[4 * q + 1][w], r2 = raw[4 * q + 2][w], r3 = raw[4 * q + 3][w];
+                uint32_t t0 = byte_perm(r1, r0, 0x05010400u);   // r0.b0 r1.b0 r0.b1 r1.b1
+                uint32_t t1 = byte_perm(r1, r0, 0x07030602u);   // r0.b2 r1.b2 r0.b3 r1.b3
+                uint32_t t2 = byte_perm(r3, r2, 0x05010400u);
+                uint32_t t3 = byte_perm(r3, r2, 0x07030602u);
+                out[4 * w + 0][q] = (int)byte_perm(t2, t0, 0x05040100u);
+                out[4 * w + 1][q] = (int)byte_perm(t2, t0, 0x07060302u);
+                out[4 * w + 2][q] = (int)byte_perm(t3, t1, 0x05040100u);
+                out[4 * w + 3][q] = (int)byte_perm(t3, t1, 0x07060302u);
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------- the kernel
+template <class DT_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int MB_, int MINB_>
+struct Tile {
+    typedef DT_ DT;
+    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, MB = MB_, MINB = MINB_;
+    static constexpr int NT = WAVES_M * WAVES_N * 64;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int BK = 128 / DT::ES;          // K elements per step
+    static constexpr int ROWB = 128 + 16;            // LDS bytes per tile row (16 bytes of padding)
+    static constexpr int STAGE = (BM + BN) * ROWB;   // one LDS buffer
+    static constexpr int LDS_BYTES = 2 * STAGE;      // double buffered
+    static constexpr int A_BLOCKS = (BM / MB) * 8;   // MB x KCH blocks of the A tile
+    static constexpr int A_IT = (A_BLOCKS + NT - 1) / NT;
+    static constexpr int B_CHUNKS = BN * 8;
+    static constexpr int B_IT = (B_CHUNKS + NT - 1) / NT;         // 16-byte chunks of the B tile per lane
+    static constexpr int AW = MB * DT::ES / 4;       // 32-bit words per loaded A vector
+    static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tiles are made of 32x32 blocks");
+};
+
+template <class T>
+__global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
+{
+    typedef typename T::DT DT;
+    typedef typename DT::elt elt;
+    typedef typename DT::acc_t acc_t;
+    typedef typename DT::accv accv;
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, ROWB = T::ROWB;
+    constexpr int TM = T::TM, TN = T::TN, MB = T::MB, KCH = DT::KCH, ES = DT::ES;
+    constexpr int A_IT = T::A_IT, B_IT = T::B_IT, AW = T::AW;
+    constexpr int MBLKS = BM / MB;                   // A blocks along m
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm0 = (wave % T::WAVES_M) * T::WM;
+    const int wn0 = (wave / T::WAVES_M) * T::WN;
+
+    // ---- which tile of C (loops L1 and L3): contiguous ranges per XCD, then column groups
+    int pid = blockIdx.x;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    if (p.xcd_remap) {
+        const int q = ntiles >> 3, r = ntiles & 7;
+        const int xcd = pid & 7, idx = pid >> 3;
+        pid = xcd * q + (xcd < r ? xcd : r) + idx;
+    }
+    const int group = p.group_m * p.tiles_n;
+    const int gid = pid / group;
+    const int first_m = gid * p.group_m;
+    const int gm = (p.tiles_m - first_m) < p.group_m ? (p.tiles_m - first_m) : p.group_m;
+    const int tm = first_m + (pid % group) % gm;
+    const int tn = (pid % group) / gm;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // ---- which part of K (loop L2, possibly split)
+    const int z = blockIdx.y;
+    const int kt_begin = z * p.ktiles_per_split;
+    int kt_end = kt_begin + p.ktiles_per_split;
+    if (kt_end > p.ktiles) kt_end = p.ktiles;
+    const int nkt = kt_end - kt_begin;
+
+    const elt *__restrict__ A = (const elt *)p.A;
+    const elt *__restrict__ B = (const elt *)p.B;
+    const bool tile_vec_a = p.vecA && (m0 + BM <= p.M);
+    const bool tile_vec_b = p.vecB && (n0 + BN <= p.N);
+
+    accv acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    int rawA[A_IT][KCH][AW];
+    v4i rawB[B_IT];
+
+    // ---- global -> registers for K step kt
+    auto load_tiles = [&](int kt) {
+        const int k0 = kt * BK;
+        const bool kfull = (k0 + BK <= p.K);
+        // A: blocks of MB (m) x KCH (k); consecutive lanes take consecutive m
+        if (tile_vec_a && kfull) {
+#pragma unroll
+            for (int it = 0; it < A_IT; ++it) {
+                const int bid = tid + it * NT;
+                if (T::A_BLOCKS % NT != 0 && bid >= T::A_BLOCKS) continue;
+                const int mblk = bid % MBLKS, kch = bid / MBLKS;
+                const elt *src = A + (int64_t)(k0 + kch * KCH) * p.lda + (m0 + mblk * MB);
+#pragma unroll
+                for (int kk = 0; kk < KCH; ++kk) {
+                    if constexpr (AW == 4) {
+                        v4i v = *(const v4i *)(src + (int64_t)kk * p.lda);
+                        rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1]; rawA[it][kk][2] = v[2]; rawA[it][kk][3] = v[3];
+                    } else if constexpr (AW == 2) {
+                        v2i v = *(const v2i *)(src + (int64_t)kk * p.lda);
+                        rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1];
+                    } else {
+                        rawA[it][kk][0] = *(const int *)(src + (int64_t)kk * p.lda);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < A_IT; ++it) {
+                const int bid = tid + it * NT;
+                if (T::A_BLOCKS % NT != 0 && bid >= T::A_BLOCKS) continue;
+                const int mblk = bid % MBLKS, kch = bid / MBLKS;
+                const int mb = m0 + mblk * MB;
+#pragma unroll
+                for (int kk = 0; kk < KCH; ++kk) {
+                    const int k = k0 + kch * KCH + kk;
+                    const elt *src = A + (int64_t)k * p.lda + mb;
+#pragma unroll
+                    for (int w = 0; w < AW; ++w) {
+                        uint32_t word = 0;
+#pragma unroll
+                        for (int e = 0; e < 4 / ES; ++e) {
+                            const int mi = w * (4 / ES) + e;
+                            uint32_t bits = 0;
+                            if (k < p.K && mb + mi < p.M) {
+                                if constexpr (ES == 4) bits = __builtin_bit_cast(uint32_t, src[mi]);
+                                else if constexpr (ES == 2) bits = (uint16_t)src[mi];
+                                else bits = (uint8_t)src[mi];
+                            }
+                            word |= bits << (8 * ES * e);
+                        }
+                        rawA[it][kk][w] = (int)word;
+                    }
+                }
+            }
+        }
+        // B: 16-byte chunks along k; 8 consecutive lanes cover one 128-byte row segment
+        if (tile_vec_b && kfull) {
+#pragma unroll
+            for (int it = 0; it < B_IT; ++it) {
+                const int cid = tid + it * NT;
+                if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
+                const int row = cid >> 3, ch = cid & 7;
+                rawB[it] = *(const v4i *)(B + (int64_t)(n0 + row) * p.ldb + (k0 + ch * KCH));
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < B_IT; ++it) {
+                const int cid = tid + it * NT;
+                if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
+                const int row = cid >> 3, ch = cid & 7;
+                const int n = n0 + row;
+                const elt *src = B + (int64_t)n * p.ldb + (k0 + ch * KCH);
+                v4i v;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    uint32_t word = 0;
+#pragma unroll
+                    for (int e = 0; e < 4 / ES; ++e) {
+                        const int ki = w * (4 / ES) + e;
+                        uint32_t bits = 0;
+                        if (n < p.N && k0 + ch * KCH + ki < p.K) {
+                            if constexpr (ES == 4) bits = __builtin_bit_cast(uint32_t, src[ki]);
+                            else if constexpr (ES == 2) bits = (uint16_t)src[ki];
+                            else bits = (uint8_t)src[ki];
+                        }
+                        word |= bits << (8 * ES * e);
+                    }
+                    v[w] = (int)word;
+                }
+                rawB[it] = v;
+            }
+        }
+    };
+
+    // ---- registers -> LDS buffer `buf` (the packing step): rows of 128 bytes, K contiguous
+    auto store_tiles = [&](int buf) {
+        unsigned char *base = smem + buf * T::STAGE;
+#pragma unroll
+        for (int it = 0; it < A_IT; ++it) {
+            const int bid = tid + it * NT;
+            if (T::A_BLOCKS % NT != 0 && bid >= T::A_BLOCKS) continue;
+            const int mblk = bid % MBLKS, kch = bid / MBLKS;
+            unsigned char *dst = base + (mblk * MB) * ROWB + kch * 16;
+            if constexpr (ES == 1) {
+                v4i out[MB];
+                Transpose<DT, MB>::all(rawA[it], out);
+#pragma unroll
+                for (int c = 0; c < MB; ++c) *(v4i *)(dst + c * ROWB) = out[c];
+            } else {
+#pragma unroll
+                for (int c = 0; c < MB; ++c) *(v4i *)(dst + c * ROWB) = Transpose<DT, MB>::chunk(rawA[it], c);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < B_IT; ++it) {
+            const int cid = tid + it * NT;
+            if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
+            const int row = cid >> 3, ch = cid & 7;
+            *(v4i *)(base + (BM + row) * ROWB + ch * 16) = rawB[it];
+        }
+    };
+
+    // ---- the micro-kernel on one LDS buffer: 4 fragment steps of 2 chunks each
+    const int frow = lane & 31, fgrp = lane >> 5;
+    auto compute = [&](int buf) {
+        const unsigned char *base = smem + buf * T::STAGE;
+        const unsigned char *pa = base + (wm0 + frow) * ROWB + fgrp * 16;
+        const unsigned char *pb = base + (BM + wn0 + frow) * ROWB + fgrp * 16;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            v4i fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = *(const v4i *)(pa + i * 32 * ROWB + s * 32);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *(const v4i *)(pb + j * 32 * ROWB + s * 32);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) Mma<DT>::run(fb[j], fa[i], acc[i][j]);
+        }
+    };
+
+    if (nkt > 0) {
+        load_tiles(kt_begin);
+        store_tiles(0);
+        __syncthreads();
+        for (int i = 0; i < nkt; ++i) {
+            const bool more = (i + 1 < nkt);
+            if (more) load_tiles(kt_begin + i + 1);
+            compute(i & 1);
+            if (more) store_tiles((i + 1) & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: lane = row m of the block, registers = its 16 columns n
+    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+    const acc_t alpha = __builtin_bit_cast(acc_t, p.alpha_bits);
+    const acc_t beta = __builtin_bit_cast(acc_t, p.beta_bits);
+    const bool use_beta = p.use_beta != 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm0 + 32 * i + frow;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int n = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * fgrp + (v & 3);
+                if (interior || (m < p.M && n < p.N)) {
+                    const acc_t a = acc[i][j][v];
+                    if (p.split > 1) {
+                        acc_t *ws = (acc_t *)p.ws;
+                        ws[((int64_t)z * p.N + n) * p.M + m] = a;
+                    } else {
+                        acc_t *c = (acc_t *)p.C + (int64_t)n * p.ldc + m;
+                        if constexpr (ES == 1) {
+                            uint32_t r = (uint32_t)alpha * (uint32_t)a;
+                            if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
+                            *c = (int)r;
+                        } else {
+                            float r = alpha * a;
+                            if (use_beta) r += beta * (*c);
+                            *c = r;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- helpers
+// Sum of the split-K partial tiles in fixed order, then the alpha/beta update.
+template <class acc_t>
+__global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ ws, acc_t *__restrict__ C, int M, int N,
+                                                     int64_t ldc, int split, uint32_t alpha_bits, uint32_t beta_bits,
+                                                     int use_beta)
+{
+    const int64_t total = (int64_t)M * N;
+    const acc_t alpha = __builtin_bit_cast(acc_t, alpha_bits);
+    const acc_t beta = __builtin_bit_cast(acc_t, beta_bits);
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        const int m = (int)(idx % M);
+        const int64_t n = idx / M;
+        acc_t *c = C + n * ldc + m;
+        if constexpr (sizeof(acc_t) == 4 && __is_same(acc_t, int)) {
+            uint32_t s = 0;
+            for (int zz = 0; zz < split; ++zz) s += (uint32_t)ws[(int64_t)zz * total + idx];
+            uint32_t r = (uint32_t)alpha * s;
+            if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
+            *c = (int)r;
+        } else {
+            acc_t s = 0;
+            for (int zz = 0; zz < split; ++zz) s += ws[(int64_t)zz * total + idx];
+            acc_t r = alpha * s;
+            if (use_beta) r += beta * (*c);
+            *c = r;
+        }
+    }
+}
+
+// C <- beta*C (K == 0 or alpha == 0); beta == 0 stores zeros without reading C.
+template <class acc_t>
+__global__ void __launch_bounds__(256) scale_kernel(acc_t *__restrict__ C, int M, int N, int64_t ldc,
+                                                    uint32_t beta_bits, int use_beta)
+{
+    const int64_t total = (int64_t)M * N;
+    const acc_t beta = __builtin_bit_cast(acc_t, beta_bits);
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        const int m = (int)(idx % M);
+        const int64_t n = idx / M;
+        acc_t *c = C + n * ldc + m;
+        if (use_beta) {
+            if constexpr (__is_same(acc_t, int)) *c = (int)((uint32_t)beta * (uint32_t)(*c));
+            else *c = beta * (*c);
+        } else {
+            *c = 0;
+        }
+    }
+}
+
+}  // namespace mig

@@ -1,0 +1,44 @@
+// Host-side view of the kernel table (no device code in this header).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+namespace mig {
+
+// One canonical problem (C column-major, A with M contiguous, B with K contiguous)
+// and how the grid covers it.
+struct Params {
+    const void *A;
+    const void *B;
+    void *C;
+    void *ws;              // partial tiles [split][N][M] when split > 1
+    int64_t lda, ldb, ldc;
+    int M, N, K;
+    int tiles_m, tiles_n;
+    int ktiles;            // number of BK steps covering K
+    int ktiles_per_split;  // BK steps per blockIdx.y slice
+    int split;             // gridDim.y
+    uint32_t alpha_bits, beta_bits;
+    int use_beta;          // beta != 0: the old C is read
+    int vecA, vecB;        // operand may be read with aligned vector loads
+    int group_m;           // tiles per column group in the tile order
+    int xcd_remap;         // deal contiguous tile ranges to the 8 XCDs
+};
+
+struct KernelInfo {
+    const char *name;
+    int BM, BN, BK;   // workgroup tile; BK = K elements per step
+    int threads;
+    int lds_bytes;
+    hipError_t (*launch)(const Params &, hipStream_t);
+};
+
+int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8
+const KernelInfo *kernel_info(int dtype, int id);  // nullptr if out of range
+
+hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
+                         uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream);
+hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
+                        hipStream_t stream);
+
+}  // namespace mig

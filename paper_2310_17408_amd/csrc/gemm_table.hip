@@ -1,0 +1,109 @@
+// Kernel table: the family of tile configurations ("one micro-kernel per
+// shape" in the paper's Sec. "Edge Cases") instantiated from the template in
+// gemm_kernel.hpp, plus the launchers the host side calls through gemm_table.h.
+#include "gemm_kernel.hpp"
+#include "gemm_table.h"
+
+namespace mig {
+
+template <class T>
+static hipError_t launch_tile(const Params &p, hipStream_t stream)
+{
+    static bool attr_done[64] = {false};          // per device: allow LDS beyond the default limit
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL(gemm_kernel<T>, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+template <class T>
+static constexpr KernelInfo info(const char *name)
+{
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>};
+}
+
+//                 dtype BM   BN  waves  MB  min workgroups per CU
+typedef Tile<F32, 128, 128, 2, 2, 4, 2> F32_128x128;
+typedef Tile<F32, 256, 128, 4, 2, 4, 1> F32_256x128;
+typedef Tile<F32, 64, 64, 2, 2, 2, 2> F32_64x64;
+typedef Tile<F16, 256, 256, 2, 2, 8, 1> F16_256x256;
+typedef Tile<F16, 128, 128, 2, 2, 8, 2> F16_128x128;
+typedef Tile<F16, 64, 64, 2, 2, 2, 2> F16_64x64;
+typedef Tile<I8, 256, 256, 2, 2, 8, 1> I8_256x256;
+typedef Tile<I8, 128, 128, 2, 2, 4, 2> I8_128x128;
+typedef Tile<I8, 64, 64, 2, 2, 4, 2> I8_64x64;
+
+static const KernelInfo k_f32[] = {
+    info<F32_128x128>("f32_128x128_w64x64"),
+    info<F32_256x128>("f32_256x128_w64x64"),
+    info<F32_64x64>("f32_64x64_w32x32"),
+};
+static const KernelInfo k_f16[] = {
+    info<F16_256x256>("f16_256x256_w128x128"),
+    info<F16_128x128>("f16_128x128_w64x64"),
+    info<F16_64x64>("f16_64x64_w32x32"),
+};
+static const KernelInfo k_i8[] = {
+    info<I8_256x256>("i8_256x256_w128x128"),
+    info<I8_128x128>("i8_128x128_w64x64"),
+    info<I8_64x64>("i8_64x64_w32x32"),
+};
+
+int kernel_count(int dtype)
+{
+    switch (dtype) {
+    case 0: return (int)(sizeof(k_f32) / sizeof(k_f32[0]));
+    case 1: return (int)(sizeof(k_f16) / sizeof(k_f16[0]));
+    case 2: return (int)(sizeof(k_i8) / sizeof(k_i8[0]));
+    default: return 0;
+    }
+}
+
+const KernelInfo *kernel_info(int dtype, int id)
+{
+    if (id < 0 || id >= kernel_count(dtype)) return nullptr;
+    return dtype == 0 ? &k_f32[id] : dtype == 1 ? &k_f16[id] : &k_i8[id];
+}
+
+static unsigned blocks_for(int64_t total)
+{
+    int64_t b = (total + 255) / 256;
+    if (b > 8192) b = 8192;
+    if (b < 1) b = 1;
+    return (unsigned)b;
+}
+
+hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
+                         uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream)
+{
+    const unsigned g = blocks_for((int64_t)M * N);
+    if (dtype == 2)
+        hipLaunchKernelGGL(reduce_kernel<int>, dim3(g), dim3(256), 0, stream, (const int *)ws, (int *)C, M, N, ldc,
+                           split, alpha_bits, beta_bits, use_beta);
+    else
+        hipLaunchKernelGGL(reduce_kernel<float>, dim3(g), dim3(256), 0, stream, (const float *)ws, (float *)C, M, N,
+                           ldc, split, alpha_bits, beta_bits, use_beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
+                        hipStream_t stream)
+{
+    const unsigned g = blocks_for((int64_t)M * N);
+    if (dtype == 2)
+        hipLaunchKernelGGL(scale_kernel<int>, dim3(g), dim3(256), 0, stream, (int *)C, M, N, ldc, beta_bits, use_beta);
+    else
+        hipLaunchKernelGGL(scale_kernel<float>, dim3(g), dim3(256), 0, stream, (float *)C, M, N, ldc, beta_bits,
+                           use_beta);
+    return hipGetLastError();
+}
+
+}  // namespace mig
