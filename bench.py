@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the GEMM library on one MI355X.
+
+One "step" is one pass over the fp32 square-GEMM workload: C = 1.5*A*B + 0.5*C,
+column-major, for M = N = K in {1024, 2048, 4096, 8192} (four library calls),
+on seeded U[-1,1) inputs that are resident in HBM before the timed region.
+The headline value is the throughput of the timed steps in TFLOP/s
+(2*M*N*K flop per GEMM).  The JSON line also carries
+  * "roofline": the fp32 MFMA kernel's achieved TFLOP/s over the timed region
+    (HIP events on the launch stream) against the fp32 matrix peak,
+  * "per_shape": each configuration's own rate (fp32 squares, fp16 squares,
+    int8 shapes, the six headline im2row shapes), % of the data type's peak,
+  * "cpu_baseline": the CPU oracle timed on a bounded slice of the 4096^3 case.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"f32": 157.3, "f16": 2516.6, "i8": 5033.2}     # dense MFMA peaks, TFLOP/s (TOPS for int8)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-shape table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; --gpus %d is not supported (use --gpus 1)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2310_17408_amd as mg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(mg.lib_path()):
+        print("bench.py: libmi_gemm.so is not built (run __graft_entry__.build())", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def dev(x):
+        t = torch.from_numpy(np.ascontiguousarray(x).reshape(-1))
+        if t.dtype == torch.uint16:
+            t = t.view(torch.int16)
+        return t.cuda()
+
+    fn = {"f32": mg.gemm_f32, "f16": mg.gemm_f16, "i8": mg.gemm_i8}
+    code = {"f32": mg.F32, "f16": mg.F16, "i8": mg.I8}
+    lay = {"col": mg.COL_MAJOR, "row": mg.ROW_MAJOR}
+
+    class Case:
+        """One GEMM with its operands on the device."""
+
+        def __init__(self, dtype, layout, M, N, K, alpha, beta, seed):
+            self.dtype, self.layout, self.M, self.N, self.K = dtype, layout, M, N, K
+            self.lda, self.ldb, self.ldc = wl.tight_ld(layout, M, K), wl.tight_ld(layout, K, N), wl.tight_ld(layout, M, N)
+            if dtype == "f32":
+                A, B = wl.uniform_f32(seed, layout, M, K), wl.uniform_f32(seed + 1, layout, K, N)
+                C = wl.uniform_f32(seed + 2, layout, M, N)
+                self.alpha, self.beta = float(alpha), float(beta)
+            elif dtype == "f16":
+                A, B = wl.normal_f16_bits(seed, layout, M, K), wl.normal_f16_bits(seed + 1, layout, K, N)
+                C = np.zeros(wl._shape(layout, M, N, self.ldc), dtype=np.float32)
+                self.alpha, self.beta = float(alpha), float(beta)
+            else:
+                A, B = wl.uniform_i8(seed, layout, M, K), wl.uniform_i8(seed + 1, layout, K, N)
+                C = np.zeros(wl._shape(layout, M, N, self.ldc), dtype=np.int32)
+                self.alpha, self.beta = int(alpha), int(beta)
+            self.host = (A, B, C)
+            self.A, self.B, self.C = dev(A), dev(B), dev(C)
+            nbytes = mg.gemm_workspace_bytes(code[dtype], M, N, K)
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+            self.flop = 2.0 * M * N * K
+
+        def run(self):
+            fn[self.dtype](lay[self.layout], self.M, self.N, self.K, self.alpha, self.A, self.lda, self.B, self.ldb,
+                           self.beta, self.C, self.ldc, self.ws, stream)
+
+        def kernel(self):
+            self.run()
+            return mg.gemm_kernel_name(code[self.dtype], mg.gemm_last_kernel_id()), mg.gemm_last_split()
+
+    def timed(cases, reps):
+        """Milliseconds for `reps` passes over `cases`, HIP events on the launch stream."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(reps):
+            for c in cases:
+                c.run()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    # ---------------- headline: the fp32 square sweep
+    sweep = [Case("f32", "col", n, n, n, 1.5, 0.5, 2000 + i) for i, n in enumerate(wl.FP32_SQUARES)]
+    kernels = [c.kernel() for c in sweep]
+    for _ in range(args.warmup):
+        for c in sweep:
+            c.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms = timed(sweep, args.steps)
+    wall = time.perf_counter() - t0
+    flop_step = sum(c.flop for c in sweep)
+    tflops = flop_step * args.steps / (ms * 1e-3) / 1e12
+    launches = len(sweep) * args.steps
+    result = {
+        "metric": "GEMM TFLOP/s (TOPS for int8) and % of MFMA peak per dtype, 1 MI355X",
+        "value": round(tflops, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms / args.steps, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "fp32 square GEMM sweep M=N=K in {1024,2048,4096,8192}, column-major, "
+                               "alpha=1.5, beta=0.5, A/B/C i.i.d. U[-1,1)",
+                   "kernels": sorted(set(k for k, _ in kernels)), "wall_s": round(wall, 3)},
+        "pct_of_peak": round(100.0 * tflops / PEAK["f32"], 2),
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 3), "peak": PEAK["f32"], "unit": "TFLOP/s",
+                     "frac": round(tflops / PEAK["f32"], 4), "traffic": None,
+                     "kernel": sorted(set(k for k, _ in kernels)), "launches": launches,
+                     "avg_launch_ms": round(ms / launches, 5)},
+    }
+    del sweep
+    torch.cuda.empty_cache()
+
+    # ---------------- each configuration on its own
+    if not args.no_extras:
+        rows = []
+
+        def measure(label, case, min_ms=40.0):
+            name, split = case.kernel()
+            for _ in range(3):
+                case.run()
+            one = timed([case], 1)
+            reps = int(max(3, min(2000, min_ms / max(one, 1e-3))))
+            best = min(timed([case], reps) / reps for _ in range(3))
+            rate = case.flop / (best * 1e-3) / 1e12
+            rows.append({"config": label, "dtype": case.dtype, "layout": case.layout, "M": case.M, "N": case.N,
+                         "K": case.K, "kernel": name, "split": split, "us": round(best * 1e3, 2),
+                         "tflops": round(rate, 2), "pct_peak": round(100.0 * rate / PEAK[case.dtype], 2)})
+
+        for i, n in enumerate(wl.FP32_SQUARES):
+            measure("c2 fp32 square", Case("f32", "col", n, n, n, 1.5, 0.5, 2000 + i))
+            torch.cuda.empty_cache()
+        for i, n in enumerate(wl.FP16_SQUARES):
+            measure("c3 fp16 square", Case("f16", "row", n, n, n, 1.0, 0.0, 3000 + i))
+            torch.cuda.empty_cache()
+        for i, (M, N, K) in enumerate(wl.IM2ROW_HEADLINE):
+            for layout in ("col", "row"):
+                measure("c4 im2row", Case("f32", layout, M, N, K, 1.0, 0.0, 4000 + i))
+        for i, (M, N, K) in enumerate(wl.INT8_SHAPES):
+            for layout in ("col", "row"):
+                measure("c5 int8", Case("i8", layout, M, N, K, 1, 0, 5000 + i))
+            torch.cuda.empty_cache()
+        result["per_shape"] = rows
+
+    # ---------------- the CPU oracle on a bounded slice of the same workload
+    if not args.no_cpu:
+        import oracle
+        n, cols = 4096, 2048
+        A, B = wl.uniform_f32(2002, "col", n, n), wl.uniform_f32(2003, "col", n, cols)
+        C = wl.uniform_f32(2004, "col", n, cols)
+        t0 = time.perf_counter()
+        oracle.gemm_f32("col", n, cols, n, np.float32(1.5), A, n, B, n, np.float32(0.5), C, n)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(2.0 * n * cols * n / dt / 1e12, 6), "unit": "TFLOP/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": "first %d columns of the 4096^3 fp32 case (alpha=1.5, beta=0.5), "
+                                            "%.1f s" % (cols, dt)}
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
