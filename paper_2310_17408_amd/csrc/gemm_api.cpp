@@ -52,7 +52,7 @@ int auto_kernel(int dtype, int64_t M, int64_t N)
         const int64_t area = (int64_t)ki->BM * ki->BN;
         const int64_t tiles = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
         if (area < smallest_area) { smallest_area = area; smallest = id; }
-        if (tiles >= NUM_CU && area > best_area) { best_area = area; best = id; }
+        if (tiles >= NUM_CU && area >= best_area) { best_area = area; best = id; }   // later entries win ties
     }
     if (dtype == MI_GEMM_F32 && best == 1) best = 0;   // 256x128 is opt-in until it is measured to win
     return best >= 0 ? best : smallest;
@@ -82,7 +82,8 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool 
 
 bool aligned16(const void *p, int64_t ld, int es)
 {
-    return ((uintptr_t)p % 16 == 0) && ((ld * es) % 16 == 0);
+    // 16-byte vectors / direct LDS transfers; lane offsets inside a transfer are 32-bit
+    return ((uintptr_t)p % 16 == 0) && ((ld * es) % 16 == 0) && (ld * es < ((int64_t)1 << 27));
 }
 
 int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t alpha_bits, bool alpha_zero,

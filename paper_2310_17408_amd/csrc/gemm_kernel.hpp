@@ -156,6 +156,99 @@ struct Tile {
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tiles are made of 32x32 blocks");
 };
 
+// Which tile of C a workgroup owns (loops L1 and L3).  Workgroups are dealt to
+// the 8 XCDs round-robin, so each XCD is given a contiguous range of the tile
+// order; within that order tiles run down columns of `group_m` tiles, so that
+// workgroups resident together share A and B panels in their XCD's L2.
+__device__ __forceinline__ void tile_coords(const Params &p, int bid, int &tm, int &tn)
+{
+    int pid = bid;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    if (p.xcd_remap) {
+        const int q = ntiles >> 3, r = ntiles & 7;
+        const int xcd = pid & 7, idx = pid >> 3;
+        pid = xcd * q + (xcd < r ? xcd : r) + idx;
+    }
+    const int group = p.group_m * p.tiles_n;
+    const int gid = pid / group;
+    const int first_m = gid * p.group_m;
+    const int gm = (p.tiles_m - first_m) < p.group_m ? (p.tiles_m - first_m) : p.group_m;
+    tm = first_m + (pid % group) % gm;
+    tn = (pid % group) / gm;
+}
+
+// Epilogue: C <- alpha*acc + beta*C, or the raw partial tile into the workspace
+// when K is split.  In every 32 x 32 block a lane holds one row m and the 16
+// columns n = 8*(v/4) + 4*(lane/32) + v%4, so the 32 lanes of a half-wave write
+// 128 contiguous bytes of a column of C.
+template <class DT, int TM, int TN>
+__device__ __forceinline__ void store_tile(typename DT::accv (&acc)[TM][TN], const Params &p, int m0, int n0, int BM,
+                                           int BN, int wm0, int wn0, int lane, int z)
+{
+    typedef typename DT::acc_t acc_t;
+    const int frow = lane & 31, fgrp = lane >> 5;
+    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+    const acc_t alpha = __builtin_bit_cast(acc_t, p.alpha_bits);
+    const acc_t beta = __builtin_bit_cast(acc_t, p.beta_bits);
+    const bool use_beta = p.use_beta != 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm0 + 32 * i + frow;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int n = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * fgrp + (v & 3);
+                if (interior || (m < p.M && n < p.N)) {
+                    const acc_t a = acc[i][j][v];
+                    if (p.split > 1) {
+                        acc_t *ws = (acc_t *)p.ws;
+                        ws[((int64_t)z * p.N + n) * p.M + m] = a;
+                    } else {
+                        acc_t *c = (acc_t *)p.C + (int64_t)n * p.ldc + m;
+                        if constexpr (DT::ES == 1) {
+                            uint32_t r = (uint32_t)alpha * (uint32_t)a;
+                            if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
+                            *c = (int)r;
+                        } else {
+                            float r = alpha * a;
+                            if (use_beta) r += beta * (*c);
+                            *c = r;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// The micro-kernel (loop L6) on one staged K step: the wave at (wm0, wn0) of the
+// workgroup tile reads its operand fragments from the LDS buffer `stage` (tile
+// rows of ROWB bytes, A rows first, then B rows; K contiguous) and updates its
+// TM x TN blocks of C held in registers.  Each of the 4 fragment steps covers
+// two 16-byte chunks of K: lanes 0-31 take the even chunk, lanes 32-63 the odd.
+template <class T>
+__device__ __forceinline__ void micro_kernel(const unsigned char *stage, int wm0, int wn0, int lane,
+                                             typename T::DT::accv (&acc)[T::TM][T::TN])
+{
+    constexpr int ROWB = T::ROWB, TM = T::TM, TN = T::TN;
+    const int frow = lane & 31, fgrp = lane >> 5;
+    const unsigned char *pa = stage + (wm0 + frow) * ROWB + fgrp * 16;
+    const unsigned char *pb = stage + (T::BM + wn0 + frow) * ROWB + fgrp * 16;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        v4i fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const v4i *)(pa + i * 32 * ROWB + s * 32);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = *(const v4i *)(pb + j * 32 * ROWB + s * 32);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) Mma<typename T::DT>::run(fb[j], fa[i], acc[i][j]);
+    }
+}
+
 template <class T>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 {
@@ -176,20 +269,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
     const int wm0 = (wave % T::WAVES_M) * T::WM;
     const int wn0 = (wave / T::WAVES_M) * T::WN;
 
-    // ---- which tile of C (loops L1 and L3): contiguous ranges per XCD, then column groups
-    int pid = blockIdx.x;
-    const int ntiles = p.tiles_m * p.tiles_n;
-    if (p.xcd_remap) {
-        const int q = ntiles >> 3, r = ntiles & 7;
-        const int xcd = pid & 7, idx = pid >> 3;
-        pid = xcd * q + (xcd < r ? xcd : r) + idx;
-    }
-    const int group = p.group_m * p.tiles_n;
-    const int gid = pid / group;
-    const int first_m = gid * p.group_m;
-    const int gm = (p.tiles_m - first_m) < p.group_m ? (p.tiles_m - first_m) : p.group_m;
-    const int tm = first_m + (pid % group) % gm;
-    const int tn = (pid % group) / gm;
+    int tm, tn;
+    tile_coords(p, blockIdx.x, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     // ---- which part of K (loop L2, possibly split)
@@ -337,25 +418,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
         }
     };
 
-    // ---- the micro-kernel on one LDS buffer: 4 fragment steps of 2 chunks each
-    const int frow = lane & 31, fgrp = lane >> 5;
-    auto compute = [&](int buf) {
-        const unsigned char *base = smem + buf * T::STAGE;
-        const unsigned char *pa = base + (wm0 + frow) * ROWB + fgrp * 16;
-        const unsigned char *pb = base + (BM + wn0 + frow) * ROWB + fgrp * 16;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            v4i fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *(const v4i *)(pa + i * 32 * ROWB + s * 32);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = *(const v4i *)(pb + j * 32 * ROWB + s * 32);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) Mma<DT>::run(fb[j], fa[i], acc[i][j]);
-        }
-    };
+    // ---- the micro-kernel on one LDS buffer
+    auto compute = [&](int buf) { micro_kernel<T>(smem + buf * T::STAGE, wm0, wn0, lane, acc); };
 
     if (nkt > 0) {
         load_tiles(kt_begin);
@@ -370,40 +434,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
         }
     }
 
-    // ---- epilogue: lane = row m of the block, registers = its 16 columns n
-    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
-    const acc_t alpha = __builtin_bit_cast(acc_t, p.alpha_bits);
-    const acc_t beta = __builtin_bit_cast(acc_t, p.beta_bits);
-    const bool use_beta = p.use_beta != 0;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm0 + 32 * i + frow;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int n = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * fgrp + (v & 3);
-                if (interior || (m < p.M && n < p.N)) {
-                    const acc_t a = acc[i][j][v];
-                    if (p.split > 1) {
-                        acc_t *ws = (acc_t *)p.ws;
-                        ws[((int64_t)z * p.N + n) * p.M + m] = a;
-                    } else {
-                        acc_t *c = (acc_t *)p.C + (int64_t)n * p.ldc + m;
-                        if constexpr (ES == 1) {
-                            uint32_t r = (uint32_t)alpha * (uint32_t)a;
-                            if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
-                            *c = (int)r;
-                        } else {
-                            float r = alpha * a;
-                            if (use_beta) r += beta * (*c);
-                            *c = r;
-                        }
-                    }
-                }
-            }
-        }
-    }
+    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z);
 }
 
 // ---------------------------------------------------------------- helpers

@@ -1,0 +1,317 @@
+// Workgroup-tile GEMM kernel for gfx950 whose packing step (Pack A / Pack B of
+// the paper's Fig. "Pseudo-code of the BLIS base GEMM algorithm") is done by
+// the memory system: operand tiles go from global memory straight into LDS
+// (16 bytes per lane, no registers in between), several stages deep, and the
+// micro-kernel reads MFMA fragments from them:
+//   * the K-contiguous operand B is staged row by row (tile row n, 128 bytes of
+//     K) and read with 16-byte LDS reads;
+//   * the M-contiguous operand A is staged as it lies in memory (tile row k, BM
+//     elements of M) and read with the transposing LDS reads of gfx950, which
+//     hand each lane consecutive K for its own m.  This replaces the register
+//     transposes of the staged kernel in gemm_kernel.hpp.
+// A 16-byte chunk is stored at a position XOR-ed with low bits of its tile row,
+// so that the lanes of one LDS read hit distinct banks; the writer applies the
+// same permutation by choosing which global chunk each lane fetches.
+// Edge tiles, a partial last K step and operands that are not 16-byte aligned
+// are staged by guarded loads through registers into the same layout.
+//
+// Canonical problem and epilogue are those of gemm_kernel.hpp.
+#pragma once
+#include "gemm_kernel.hpp"
+
+namespace mig {
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+#define MIG_LDS __attribute__((address_space(3)))
+
+template <class DT_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int KSTEPS_, int NSTAGE_, int MINB_>
+struct DmaTile {
+    typedef DT_ DT;
+    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, MINB = MINB_;
+    static constexpr int KSTEPS = KSTEPS_;              // fragment steps (2 chunks of K each) per stage
+    static constexpr int NSTAGE = NSTAGE_;              // LDS stages; NSTAGE-1 K steps are in flight
+    static constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int ES = DT::ES, KCH = DT::KCH;
+    static constexpr int BK = 2 * KCH * KSTEPS;         // K elements per stage
+    static constexpr int B_ROWB = 32 * KSTEPS;          // bytes of one row of the B tile
+    static constexpr int B_CPR = 2 * KSTEPS;            // 16-byte chunks per B row
+    static constexpr int B_RP256 = 16 / B_CPR;          // B rows per 256 bytes (one pass over the LDS banks)
+    static constexpr int A_ROWB = BM * ES;              // bytes of one k-row of the A tile
+    static constexpr int A_CPR = A_ROWB / 16;           // 16-byte chunks per k-row
+    static constexpr int A_BYTES = BK * A_ROWB;
+    static constexpr int B_BYTES = BN * B_ROWB;
+    static constexpr int STAGE = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static constexpr int A_INST = A_BYTES / 1024 / NW;  // 1 KiB transfers per wave and stage
+    static constexpr int B_INST = B_BYTES / 1024 / NW;
+    static constexpr int A_ROWS_PER_INST = 1024 / A_ROWB;
+    static constexpr int B_ROWS_PER_INST = 1024 / B_ROWB;
+    static constexpr int INST = A_INST + B_INST;
+    // transposing read: a group of 16 lanes reads KH k-rows x 16 m; LPR lanes share a row
+    static constexpr int LPR = 2 * ES;                  // 4 (16-bit) or 2 (8-bit)
+    static constexpr int KH = 16 / LPR;                 // k-rows per transposing read: 4 or 8
+    // A chunk swizzle: chunk ^ ((k & SWZ_MASK) << SWZ_SHIFT) spreads KH consecutive k-rows
+    static constexpr int SWZ_SHIFT = (ES == 2) ? 2 : 1;
+    static constexpr int SWZ_MASK_FULL = KH - 1;
+    static constexpr int SWZ_MASK = ((SWZ_MASK_FULL << SWZ_SHIFT) < A_CPR) ? SWZ_MASK_FULL : (SWZ_MASK_FULL >> 1);
+    static_assert(KSTEPS == 2 || KSTEPS == 4, "a B row holds 4 or 8 chunks");
+    static_assert(NSTAGE >= 2 && (NSTAGE - 1) * INST <= 63, "transfers in flight must fit the counter");
+    static_assert(ES == 1 || ES == 2, "transposing LDS reads exist for 8- and 16-bit elements");
+    static_assert(A_ROWB <= 1024 && 1024 % A_ROWB == 0, "a 1 KiB transfer must cover whole k-rows of A");
+    static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tiles must split evenly over the waves");
+    static_assert((SWZ_MASK << SWZ_SHIFT) < A_CPR, "swizzle must stay inside a row");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tiles are made of 32x32 blocks");
+};
+
+// One 1 KiB global -> LDS transfer by the calling wave: lane l writes LDS bytes
+// [lds_addr + 16*l, +16) with the 16 bytes at base + lane_off (base is uniform,
+// lane_off a 32-bit byte offset of the lane).
+__device__ __forceinline__ void lds_dma16(const void *base, uint32_t lane_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_off), "s"(base)
+                 : "memory");
+}
+
+// 16 bytes along the contiguous dimension with the first `valid` elements taken
+// from memory and the rest zero (edge tiles, K tail, unaligned operands).
+template <class DT>
+__device__ __forceinline__ v4i guarded_chunk(const typename DT::elt *src, int valid)
+{
+    constexpr int ES = DT::ES;
+    v4i v;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int e = 0; e < 4 / ES; ++e) {
+            const int idx = w * (4 / ES) + e;
+            uint32_t bits = 0;
+            if (idx < valid) {
+                if constexpr (ES == 4) bits = __builtin_bit_cast(uint32_t, src[idx]);
+                else if constexpr (ES == 2) bits = (uint16_t)src[idx];
+                else bits = (uint8_t)src[idx];
+            }
+            word |= bits << (8 * ES * e);
+        }
+        v[w] = (int)word;
+    }
+    return v;
+}
+
+template <class T>
+__global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p)
+{
+    typedef typename T::DT DT;
+    typedef typename DT::elt elt;
+    typedef typename DT::accv accv;
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NW = T::NW, ES = T::ES, KCH = T::KCH;
+    constexpr int TM = T::TM, TN = T::TN, A_ROWB = T::A_ROWB, A_CPR = T::A_CPR;
+    constexpr int LPR = T::LPR, KH = T::KH;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(MIG_LDS unsigned char *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave % T::WAVES_M) * T::WM;
+    const int wn0 = (wave / T::WAVES_M) * T::WN;
+
+    int tm, tn;
+    tile_coords(p, blockIdx.x, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int z = blockIdx.y;
+    const int kt_begin = z * p.ktiles_per_split;
+    int kt_end = kt_begin + p.ktiles_per_split;
+    if (kt_end > p.ktiles) kt_end = p.ktiles;
+    const int nkt = kt_end - kt_begin;
+
+    const elt *__restrict__ A = (const elt *)p.A;
+    const elt *__restrict__ B = (const elt *)p.B;
+    const bool tile_fast_a = p.vecA && (m0 + BM <= p.M);
+    const bool tile_fast_b = p.vecB && (n0 + BN <= p.N);
+
+    // ---- staging: which chunk of the A and B tiles this lane moves in transfer j
+    // A: transfer block b = wave + NW*j covers k-rows b*A_ROWS_PER_INST ...; lane -> (row, physical chunk)
+    const int a_row_in = lane / A_CPR, a_pch = lane % A_CPR;
+    // B: transfer block b covers B_ROWS_PER_INST tile rows; lane -> (row, physical chunk)
+    const int b_row_in = lane / T::B_CPR, b_pch = lane % T::B_CPR;
+    // The swizzle term of a lane's row does not depend on j (NW transfers apart the row pattern
+    // repeats), so a lane's byte offset from the block's first element is the same in every transfer.
+    static_assert((NW * T::A_ROWS_PER_INST) % (T::SWZ_MASK + 1) == 0, "A swizzle must repeat every NW blocks");
+    static_assert((NW * T::B_ROWS_PER_INST) % (T::B_RP256 * T::B_CPR) == 0, "B swizzle must repeat every NW blocks");
+    const int a_ch = a_pch ^ (((wave * T::A_ROWS_PER_INST + a_row_in) & T::SWZ_MASK) << T::SWZ_SHIFT);
+    const int b_ch = b_pch ^ (((wave * T::B_ROWS_PER_INST + b_row_in) / T::B_RP256) % T::B_CPR);
+    const uint32_t a_lane_off = (uint32_t)(((int64_t)a_row_in * p.lda + a_ch * (16 / ES)) * ES);
+    const uint32_t b_lane_off = (uint32_t)(((int64_t)b_row_in * p.ldb + b_ch * KCH) * ES);
+    const int64_t a_blk_stride = (int64_t)NW * T::A_ROWS_PER_INST * p.lda * ES;   // bytes between transfers j, j+1
+    const int64_t b_blk_stride = (int64_t)NW * T::B_ROWS_PER_INST * p.ldb * ES;
+    const unsigned char *a_wave = (const unsigned char *)A + ((int64_t)wave * T::A_ROWS_PER_INST * p.lda + m0) * ES;
+    const unsigned char *b_wave = (const unsigned char *)B + ((int64_t)(n0 + wave * T::B_ROWS_PER_INST) * p.ldb) * ES;
+
+    // all transfers of one K step, operands fully inside the matrices and 16-byte aligned
+    auto stage_dma = [&](int kt, int buf) {
+        const unsigned char *ab = a_wave + (int64_t)kt * BK * p.lda * ES;
+        const unsigned char *bb = b_wave + (int64_t)kt * BK * ES;
+        const uint32_t la = lds_base + buf * T::STAGE + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < T::A_INST; ++j) lds_dma16(ab + j * a_blk_stride, a_lane_off, la + j * NW * 1024);
+#pragma unroll
+        for (int j = 0; j < T::B_INST; ++j)
+            lds_dma16(bb + j * b_blk_stride, b_lane_off, la + T::A_BYTES + j * NW * 1024);
+    };
+
+    // the same chunks through registers, with zero fill: edge tiles, partial K step, unaligned operands
+    auto stage_guarded = [&](int kt, int buf, bool dma_a, bool dma_b) {
+        const int k0 = kt * BK;
+        const uint32_t sbase = buf * T::STAGE;
+        if (dma_a) {
+            const unsigned char *ab = a_wave + (int64_t)kt * BK * p.lda * ES;
+#pragma unroll
+            for (int j = 0; j < T::A_INST; ++j)
+                lds_dma16(ab + j * a_blk_stride, a_lane_off, lds_base + sbase + (wave + NW * j) * 1024);
+        } else {
+#pragma unroll
+            for (int j = 0; j < T::A_INST; ++j) {
+                const int blk = wave + NW * j;
+                const int k = blk * T::A_ROWS_PER_INST + a_row_in;             // tile-local k-row
+                const int m = m0 + a_ch * (16 / ES);
+                const elt *src = A + (int64_t)(k0 + k) * p.lda + m;
+                int valid = (k0 + k < p.K) ? (p.M - m) : 0;
+                valid = valid > 16 / ES ? 16 / ES : valid;
+                *(v4i *)(smem + sbase + blk * 1024 + lane * 16) = guarded_chunk<DT>(src, valid);
+            }
+        }
+        if (dma_b) {
+            const unsigned char *bb = b_wave + (int64_t)kt * BK * ES;
+#pragma unroll
+            for (int j = 0; j < T::B_INST; ++j)
+                lds_dma16(bb + j * b_blk_stride, b_lane_off, lds_base + sbase + T::A_BYTES + (wave + NW * j) * 1024);
+        } else {
+#pragma unroll
+            for (int j = 0; j < T::B_INST; ++j) {
+                const int blk = wave + NW * j;
+                const int r = blk * T::B_ROWS_PER_INST + b_row_in;              // tile row n
+                const int k = k0 + b_ch * KCH;
+                const elt *src = B + (int64_t)(n0 + r) * p.ldb + k;
+                int valid = (n0 + r < p.N) ? (p.K - k) : 0;
+                valid = valid > KCH ? KCH : valid;
+                *(v4i *)(smem + sbase + T::A_BYTES + blk * 1024 + lane * 16) = guarded_chunk<DT>(src, valid);
+            }
+        }
+    };
+    auto stage_tiles = [&](int kt, int buf) {
+        const bool kfull = ((kt + 1) * BK <= p.K);
+        stage_guarded(kt, buf, tile_fast_a && kfull, tile_fast_b && kfull);
+    };
+
+    // ---- fragment addresses of this lane inside a stage
+    const int frow = lane & 31, fgrp = lane >> 5;
+    // B: row wn0 + 32*j + frow, logical chunk 2*s + fgrp
+    uint32_t boff[T::KSTEPS];
+    {
+        const int x = (frow / T::B_RP256) % T::B_CPR;   // swizzle of the row: wn0 and 32*j are multiples of 16
+#pragma unroll
+        for (int s = 0; s < T::KSTEPS; ++s)
+            boff[s] = T::A_BYTES + (wn0 + frow) * T::B_ROWB + (((2 * s + fgrp) ^ x) << 4);
+    }
+    // A: the 16-lane group q = lane/16 serves m-half q%2 of the block for k-group q/2 (= fgrp);
+    // inside it, lane t addresses k-row t/LPR and the (t%LPR)-th 8-byte piece of 16 m.
+    uint32_t aoff[TM];
+    {
+        const int t = lane & 15, mh = (lane >> 4) & 1;
+        const int kr = t / LPR, ml = t % LPR;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mbyte = (wm0 + 32 * i + 16 * mh) * ES + 8 * ml;
+            const int ch = (mbyte >> 4) ^ ((kr & T::SWZ_MASK) << T::SWZ_SHIFT);
+            aoff[i] = (KCH * fgrp + kr) * A_ROWB + (ch << 4) + (mbyte & 15);
+        }
+    }
+
+    accv acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    // ---- the micro-kernel on one stage: KSTEPS fragment steps of 2*KCH consecutive k
+    auto compute = [&](int buf) {
+        const unsigned char *stage = smem + buf * T::STAGE;
+#pragma unroll
+        for (int s = 0; s < T::KSTEPS; ++s) {
+            v4i fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                // two transposing reads give this lane KCH consecutive k of its m
+                const unsigned char *q0 = stage + aoff[i] + (2 * KCH * s) * A_ROWB;
+                const unsigned char *q1 = q0 + KH * A_ROWB;
+                if constexpr (ES == 2) {
+                    v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
+                    v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
+                    fa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                } else {
+                    v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
+                    v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
+                    fa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) Mma<DT>::run(fb[j], fa[i], acc[i][j]);
+        }
+    };
+
+    // ---- K loop over NSTAGE LDS stages: while step i is multiplied, the transfers of
+    // steps i+1 .. i+NSTAGE-1 are in flight.  The first `nfast` steps of this workgroup are
+    // direct transfers only; the hot loop runs while every step in flight is one of them.
+    constexpr int D = T::NSTAGE - 1;
+    int nfast = 0;
+    if (tile_fast_a && tile_fast_b) {
+        nfast = p.K / BK - kt_begin;
+        nfast = nfast < 0 ? 0 : (nfast > nkt ? nkt : nfast);
+    }
+    if (nkt > 0) {
+#pragma unroll
+        for (int t = 0; t < D; ++t)
+            if (t < nkt) stage_tiles(kt_begin + t, t);
+        int buf = 0, nbuf = D;           // stage of step i, stage of step i + D
+        int i = 0;
+        for (; i + D < nfast; ++i) {
+            // This wave's transfers of step i are done when at most those of the D-1 later steps
+            // are outstanding (transfers complete in order) ...
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"((D - 1) * T::INST) : "memory");
+            // ... then everybody's are, and everybody has finished reading the stage of step i-1,
+            // which the transfers of step i+D now overwrite.
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            stage_dma(kt_begin + i + D, nbuf);
+            compute(buf);
+            buf = (buf + 1 == T::NSTAGE) ? 0 : buf + 1;
+            nbuf = (nbuf + 1 == T::NSTAGE) ? 0 : nbuf + 1;
+        }
+        for (; i < nkt; ++i) {
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (i + D < nkt) stage_tiles(kt_begin + i + D, nbuf);
+            compute(buf);
+            buf = (buf + 1 == T::NSTAGE) ? 0 : buf + 1;
+            nbuf = (nbuf + 1 == T::NSTAGE) ? 0 : nbuf + 1;
+        }
+    }
+
+    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z);
+}
+
+}  // namespace mig

@@ -2,6 +2,7 @@
 // shape" in the paper's Sec. "Edge Cases") instantiated from the template in
 // gemm_kernel.hpp, plus the launchers the host side calls through gemm_table.h.
 #include "gemm_kernel.hpp"
+#include "gemm_kernel_dma.hpp"
 #include "gemm_table.h"
 
 namespace mig {
@@ -25,12 +26,37 @@ static hipError_t launch_tile(const Params &p, hipStream_t stream)
 }
 
 template <class T>
+static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
+{
+    static bool attr_done[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL(gemm_kernel_dma<T>, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+template <class T>
+static constexpr KernelInfo info_dma(const char *name)
+{
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>};
+}
+
+template <class T>
 static constexpr KernelInfo info(const char *name)
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>};
 }
 
-//                 dtype BM   BN  waves  MB  min workgroups per CU
+// Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU
+// Direct-to-LDS:    dtype BM   BN  waves  fragment steps per stage, stages, min workgroups per CU
 typedef Tile<F32, 128, 128, 2, 2, 4, 2> F32_128x128;
 typedef Tile<F32, 256, 128, 4, 2, 4, 1> F32_256x128;
 typedef Tile<F32, 64, 64, 2, 2, 2, 2> F32_64x64;
@@ -50,11 +76,15 @@ static const KernelInfo k_f16[] = {
     info<F16_256x256>("f16_256x256_w128x128"),
     info<F16_128x128>("f16_128x128_w64x64"),
     info<F16_64x64>("f16_64x64_w32x32"),
+    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma"),
+    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma"),
 };
 static const KernelInfo k_i8[] = {
     info<I8_256x256>("i8_256x256_w128x128"),
     info<I8_128x128>("i8_128x128_w64x64"),
     info<I8_64x64>("i8_64x64_w32x32"),
+    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma"),
+    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma"),
 };
 
 int kernel_count(int dtype)
