@@ -1,0 +1,93 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host logic (argument checks, quick returns, workspace
+sizing, kernel table) behaves as include/mi_gemm.h says.  Nothing here launches
+a kernel: every call returns before the first HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2310_17408_amd as mg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "mi_gemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gemm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(mg.lib_path())
+    names = _declared_functions()
+    assert {"gemm_f32", "gemm_f16", "gemm_i8", "gemm_workspace_bytes", "gemm_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), "symbol %s is declared but not exported" % n
+
+
+def test_kernel_table():
+    for dtype in (mg.F32, mg.F16, mg.I8):
+        n = mg.gemm_kernel_count(dtype)
+        assert n >= 3
+        names = [mg.gemm_kernel_name(dtype, i) for i in range(n)]
+        assert len(set(names)) == n and all(names)
+        assert mg.gemm_kernel_name(dtype, n) == ""
+        assert mg.gemm_force_kernel(dtype, n, 0) == -1
+        assert mg.gemm_force_kernel(dtype, 0, 3) == 0
+        assert mg.gemm_force_kernel(dtype, -1, 0) == 0
+    assert mg.gemm_kernel_count(7) == 0
+    assert mg.gemm_force_kernel(5, 0, 0) == -1
+
+
+@pytest.mark.parametrize("fn", [mg.gemm_f32, mg.gemm_f16, mg.gemm_i8])
+def test_argument_errors_return_before_any_launch(fn):
+    P = 0x1000            # never dereferenced: every call below fails validation or returns early
+    ok = dict(layout=mg.COL_MAJOR, M=8, N=9, K=10, alpha=1, A=P, lda=8, B=P, ldb=10, beta=0, C=P, ldc=8)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return fn(a["layout"], a["M"], a["N"], a["K"], a["alpha"], a["A"], a["lda"], a["B"], a["ldb"], a["beta"],
+                  a["C"], a["ldc"], None, 0, check=False)
+
+    assert call(layout=2) == -1
+    assert call(M=-1) == -2
+    assert call(N=-5) == -3
+    assert call(K=-1) == -4
+    assert call(M=2 ** 31) == -2
+    assert call(lda=7) == -7
+    assert call(ldb=9) == -9
+    assert call(ldc=7) == -12
+    assert call(layout=mg.ROW_MAJOR, lda=9, ldb=9, ldc=9) == -7       # row-major: lda >= K
+    assert call(layout=mg.ROW_MAJOR, lda=10, ldb=8, ldc=9) == -9      # ldb >= N
+    assert call(layout=mg.ROW_MAJOR, lda=10, ldb=9, ldc=8) == -12     # ldc >= N
+    assert call(A=None) == -6
+    assert call(B=None) == -8
+    assert call(C=None) == -11
+    # quick returns that touch nothing
+    assert call(M=0, lda=1, ldc=1) == 0
+    assert call(N=0) == 0
+    assert call(M=0, C=None, lda=1, ldc=1) == 0
+    assert call(alpha=0, beta=1, A=None, B=None) == 0
+    for status in range(0, -16, -1):
+        assert mg.gemm_status_string(status)
+    with pytest.raises(mg.GemmError):
+        fn(mg.COL_MAJOR, 8, 9, 10, 1, P, 7, P, 10, 0, P, 8)
+
+
+def test_misaligned_workspace_is_rejected():
+    lib = mg.load()
+    rc = lib.gemm_f32(0, 8, 8, 8, 1.0, 0x1000, 8, 0x1000, 8, 0.0, 0x1000, 8, 0x1004, 1 << 20, None)
+    assert rc == -13
+
+
+def test_workspace_bytes():
+    # big squares never split K; skinny long-K problems do, and the bound covers split * M * N * 4
+    assert mg.gemm_workspace_bytes(mg.F32, 8192, 8192, 8192) == 0
+    assert mg.gemm_workspace_bytes(mg.F32, 0, 10, 10) == 0
+    assert mg.gemm_workspace_bytes(9, 10, 10, 10) == 0
+    w = mg.gemm_workspace_bytes(mg.F32, 49, 512, 4608)
+    assert w >= 2 * 49 * 512 * 4 and w % (49 * 512 * 4) == 0
+    assert mg.gemm_workspace_bytes(mg.F32, 49, 512, 4608) == mg.gemm_workspace_bytes(mg.F32, 512, 49, 4608)
