@@ -43,8 +43,10 @@
  * value is a HIP error code from the launch.  gemm_status_string() describes
  * any of them.
  *
- * Results are deterministic: the same call on the same data gives the same
- * bits, whatever the workspace size (a split K loop is reduced in fixed order).
+ * Results are deterministic: the same call (same arguments, workspace size
+ * included) on the same data gives the same bits, because a split K loop is
+ * reduced in fixed order.  A different workspace size may change the split and
+ * with it the floating-point rounding order; int8 results never depend on it.
  */
 #ifndef MI_GEMM_H
 #define MI_GEMM_H
