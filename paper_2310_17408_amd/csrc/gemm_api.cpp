@@ -38,24 +38,23 @@ int auto_split(int64_t tiles, int64_t ktiles)
 }
 
 // Tile selection (the analogue of choosing the micro-kernel size that matches
-// the problem, paper Secs. "Edge Cases" and "Squared Matrices"): the largest
-// tile that still gives every CU a workgroup, else the smallest tile.
+// the problem, paper Secs. "Edge Cases" and "Squared Matrices"): configurations
+// are tried in order of falling priority and the first one that yields enough
+// tiles to keep the 256 CUs busy wins; small problems fall through to the
+// smallest tile, which is then helped by splitting K.
 int auto_kernel(int dtype, int64_t M, int64_t N)
 {
     const int n = kernel_count(dtype);
-    int best = -1;
-    int64_t best_area = 0;
-    int smallest = 0;
-    int64_t smallest_area = INT64_MAX;
+    int best = -1, best_prio = 0;
+    int fallback = 0, fallback_prio = INT_MAX;
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        const int64_t area = (int64_t)ki->BM * ki->BN;
+        if (ki->prio <= 0) continue;
         const int64_t tiles = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
-        if (area < smallest_area) { smallest_area = area; smallest = id; }
-        if (tiles >= NUM_CU && area >= best_area) { best_area = area; best = id; }   // later entries win ties
+        if (ki->prio < fallback_prio) { fallback_prio = ki->prio; fallback = id; }
+        if (tiles >= ki->min_tiles && ki->prio > best_prio) { best_prio = ki->prio; best = id; }
     }
-    if (dtype == MI_GEMM_F32 && best == 1) best = 0;   // 256x128 is opt-in until it is measured to win
-    return best >= 0 ? best : smallest;
+    return best >= 0 ? best : fallback;
 }
 
 Choice choose(int dtype, int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool have_ws)

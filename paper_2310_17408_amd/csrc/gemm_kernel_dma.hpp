@@ -29,7 +29,7 @@ struct DmaTile {
     typedef DT_ DT;
     static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, MINB = MINB_;
     static constexpr int KSTEPS = KSTEPS_;              // fragment steps (2 chunks of K each) per stage
-    static constexpr int NSTAGE = NSTAGE_;              // LDS stages; NSTAGE-1 K steps are in flight
+    static constexpr int NSTAGE = NSTAGE_;              // LDS stages: one being multiplied, the others in flight
     static constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     static constexpr int TM = WM / 32, TN = WN / 32;
@@ -57,7 +57,7 @@ struct DmaTile {
     static constexpr int SWZ_MASK_FULL = KH - 1;
     static constexpr int SWZ_MASK = ((SWZ_MASK_FULL << SWZ_SHIFT) < A_CPR) ? SWZ_MASK_FULL : (SWZ_MASK_FULL >> 1);
     static_assert(KSTEPS == 2 || KSTEPS == 4, "a B row holds 4 or 8 chunks");
-    static_assert(NSTAGE >= 2 && (NSTAGE - 1) * INST <= 63, "transfers in flight must fit the counter");
+    static_assert(NSTAGE >= 2 && (NSTAGE - 2) * INST <= 63, "transfers in flight must fit the counter");
     static_assert(ES == 1 || ES == 2, "transposing LDS reads exist for 8- and 16-bit elements");
     static_assert(A_ROWB <= 1024 && 1024 % A_ROWB == 0, "a 1 KiB transfer must cover whole k-rows of A");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tiles must split evenly over the waves");
@@ -74,6 +74,18 @@ __device__ __forceinline__ void lds_dma16(const void *base, uint32_t lane_off, u
                  :
                  : "s"(lds_addr), "v"(lane_off), "s"(base)
                  : "memory");
+}
+
+// Wait until at most N of this wave's vector-memory operations (the transfers above complete in
+// order) and none of its LDS operations are outstanding.  s_waitcnt immediate of gfx9:
+// vmcnt = bits 3:0 and 15:14, expcnt = bits 6:4 (7 = no wait), lgkmcnt = bits 11:8.
+template <int N>
+__device__ __forceinline__ void wait_transfers()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+    asm volatile("" ::: "memory");
 }
 
 // 16 bytes along the contiguous dimension with the first `valid` elements taken
@@ -242,40 +254,54 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    // ---- the micro-kernel on one stage: KSTEPS fragment steps of 2*KCH consecutive k
-    auto compute = [&](int buf) {
+    // ---- the micro-kernel: KSTEPS fragment steps of 2*KCH consecutive k per stage.  Fragments are
+    // double buffered in registers: while the MFMAs of one step run, the LDS reads of the next are
+    // in flight, also across the barrier that ends a K step.
+    v4i fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int buf, int s, v4i (&xa)[TM], v4i (&xb)[TN]) {
         const unsigned char *stage = smem + buf * T::STAGE;
 #pragma unroll
-        for (int s = 0; s < T::KSTEPS; ++s) {
-            v4i fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                // two transposing reads give this lane KCH consecutive k of its m
-                const unsigned char *q0 = stage + aoff[i] + (2 * KCH * s) * A_ROWB;
-                const unsigned char *q1 = q0 + KH * A_ROWB;
-                if constexpr (ES == 2) {
-                    v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
-                    v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
-                    fa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
-                } else {
-                    v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
-                    v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
-                    fa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
-                }
+        for (int i = 0; i < TM; ++i) {
+            // two transposing reads give this lane KCH consecutive k of its m
+            const unsigned char *q0 = stage + aoff[i] + (2 * KCH * s) * A_ROWB;
+            const unsigned char *q1 = q0 + KH * A_ROWB;
+            if constexpr (ES == 2) {
+                v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
+                v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
+                xa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
+                v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
+                xa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
             }
+        }
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
+        for (int j = 0; j < TN; ++j) xb[j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
+    };
+    auto mma_step = [&](v4i (&xa)[TM], v4i (&xb)[TN]) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) Mma<DT>::run(fb[j], fa[i], acc[i][j]);
+            for (int j = 0; j < TN; ++j) Mma<DT>::run(xb[j], xa[i], acc[i][j]);
+    };
+    // all but the last step of the stage `buf`; on entry the fragments of its step 0 are in set 0
+    auto steps_but_last = [&](int buf) {
+#pragma unroll
+        for (int s = 0; s + 1 < T::KSTEPS; ++s) {
+            load_frags(buf, s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+            mma_step(fa[s & 1], fb[s & 1]);
+            __builtin_amdgcn_sched_barrier(0);   // keep each step's reads and MFMAs together
         }
     };
+    constexpr int LAST = (T::KSTEPS - 1) & 1;   // register set that holds the last step (KSTEPS is even)
 
-    // ---- K loop over NSTAGE LDS stages: while step i is multiplied, the transfers of
-    // steps i+1 .. i+NSTAGE-1 are in flight.  The first `nfast` steps of this workgroup are
-    // direct transfers only; the hot loop runs while every step in flight is one of them.
-    constexpr int D = T::NSTAGE - 1;
+    // ---- K loop over NSTAGE LDS stages.  When the LDS reads of step i's last fragments have been
+    // issued, the wave waits for its transfers of step i+1, meets the others at the barrier (now
+    // step i+1 is visible to all, and nobody reads the stage of step i any more), refills that stage
+    // with step i+NSTAGE, starts reading step i+1 and only then issues the last MFMAs of step i,
+    // which cover the latency of those reads.  The first `nfast` steps of this workgroup are direct
+    // transfers only; the hot loop runs while every step in flight is one of them.
+    constexpr int NS = T::NSTAGE;
     int nfast = 0;
     if (tile_fast_a && tile_fast_b) {
         nfast = p.K / BK - kt_begin;
@@ -283,31 +309,41 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     }
     if (nkt > 0) {
 #pragma unroll
-        for (int t = 0; t < D; ++t)
+        for (int t = 0; t < NS; ++t)
             if (t < nkt) stage_tiles(kt_begin + t, t);
-        int buf = 0, nbuf = D;           // stage of step i, stage of step i + D
+        wait_transfers<0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        load_frags(0, 0, fa[0], fb[0]);
+        int buf = 0;
         int i = 0;
-        for (; i + D < nfast; ++i) {
-            // This wave's transfers of step i are done when at most those of the D-1 later steps
-            // are outstanding (transfers complete in order) ...
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"((D - 1) * T::INST) : "memory");
-            // ... then everybody's are, and everybody has finished reading the stage of step i-1,
-            // which the transfers of step i+D now overwrite.
+        for (; i + NS < nfast; ++i) {
+            const int nxt = (buf + 1 == NS) ? 0 : buf + 1;
+            steps_but_last(buf);
+            // transfers complete in order: step i+1 is done when at most those of the NS-2 later
+            // steps are outstanding; lgkmcnt(0): this wave's reads of stage `buf` have returned
+            wait_transfers<(NS - 2) * T::INST>();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            stage_dma(kt_begin + i + D, nbuf);
-            compute(buf);
-            buf = (buf + 1 == T::NSTAGE) ? 0 : buf + 1;
-            nbuf = (nbuf + 1 == T::NSTAGE) ? 0 : nbuf + 1;
+            stage_dma(kt_begin + i + NS, buf);
+            load_frags(nxt, 0, fa[0], fb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_step(fa[LAST], fb[LAST]);
+            buf = nxt;
         }
         for (; i < nkt; ++i) {
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            if (i + D < nkt) stage_tiles(kt_begin + i + D, nbuf);
-            compute(buf);
-            buf = (buf + 1 == T::NSTAGE) ? 0 : buf + 1;
-            nbuf = (nbuf + 1 == T::NSTAGE) ? 0 : nbuf + 1;
+            const int nxt = (buf + 1 == NS) ? 0 : buf + 1;
+            steps_but_last(buf);
+            if (i + 1 < nkt) {
+                wait_transfers<0>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (i + NS < nkt) stage_tiles(kt_begin + i + NS, buf);
+                load_frags(nxt, 0, fa[0], fb[0]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            mma_step(fa[LAST], fb[LAST]);
+            buf = nxt;
         }
     }
 

@@ -31,6 +31,11 @@ struct KernelInfo {
     int threads;
     int lds_bytes;
     hipError_t (*launch)(const Params &, hipStream_t);
+    // Automatic selection: among the configurations with prio > 0, in order of falling prio, the
+    // first one whose tile count for the problem reaches min_tiles is taken; if none does, the
+    // one with the lowest prio.  prio 0: only by explicit request.
+    int prio;
+    int min_tiles;
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8

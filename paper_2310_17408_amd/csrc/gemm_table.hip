@@ -3,6 +3,7 @@
 // gemm_kernel.hpp, plus the launchers the host side calls through gemm_table.h.
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
+#include "gemm_kernel_dma32.hpp"
 #include "gemm_table.h"
 
 namespace mig {
@@ -44,15 +45,39 @@ static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
 }
 
 template <class T>
-static constexpr KernelInfo info_dma(const char *name)
+static constexpr KernelInfo info_dma(const char *name, int prio, int min_tiles)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, min_tiles};
 }
 
 template <class T>
-static constexpr KernelInfo info(const char *name)
+static hipError_t launch_tile_dma32(const Params &p, hipStream_t stream)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>};
+    static bool attr_done[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma32<T>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL(gemm_kernel_dma32<T>, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+template <class T>
+static constexpr KernelInfo info_dma32(const char *name, int prio, int min_tiles)
+{
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, min_tiles};
+}
+
+template <class T>
+static constexpr KernelInfo info(const char *name, int prio, int min_tiles)
+{
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, min_tiles};
 }
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU
@@ -67,24 +92,28 @@ typedef Tile<I8, 256, 256, 2, 2, 8, 1> I8_256x256;
 typedef Tile<I8, 128, 128, 2, 2, 4, 2> I8_128x128;
 typedef Tile<I8, 64, 64, 2, 2, 4, 2> I8_64x64;
 
+// name, priority in the automatic selection, fewest tiles for which it is taken (256 CUs)
 static const KernelInfo k_f32[] = {
-    info<F32_128x128>("f32_128x128_w64x64"),
-    info<F32_256x128>("f32_256x128_w64x64"),
-    info<F32_64x64>("f32_64x64_w32x32"),
+    info<F32_128x128>("f32_128x128_w64x64", 0, 0),
+    info<F32_256x128>("f32_256x128_w64x64", 0, 0),
+    info<F32_64x64>("f32_64x64_w32x32", 1, 0),
+    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 0),
+    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 3, 512),
+    info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 0),
 };
 static const KernelInfo k_f16[] = {
-    info<F16_256x256>("f16_256x256_w128x128"),
-    info<F16_128x128>("f16_128x128_w64x64"),
-    info<F16_64x64>("f16_64x64_w32x32"),
-    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma"),
-    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma"),
+    info<F16_256x256>("f16_256x256_w128x128", 0, 0),
+    info<F16_128x128>("f16_128x128_w64x64", 0, 0),
+    info<F16_64x64>("f16_64x64_w32x32", 1, 0),
+    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 2, 256),
+    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 3, 256),
 };
 static const KernelInfo k_i8[] = {
-    info<I8_256x256>("i8_256x256_w128x128"),
-    info<I8_128x128>("i8_128x128_w64x64"),
-    info<I8_64x64>("i8_64x64_w32x32"),
-    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma"),
-    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma"),
+    info<I8_256x256>("i8_256x256_w128x128", 0, 0),
+    info<I8_128x128>("i8_128x128_w64x64", 0, 0),
+    info<I8_64x64>("i8_64x64_w32x32", 1, 0),
+    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 2, 256),
+    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 3, 256),
 };
 
 int kernel_count(int dtype)
