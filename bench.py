@@ -24,6 +24,12 @@ if ROOT not in sys.path:
 
 PEAK = {"f32": 157.3, "f16": 2516.6, "i8": 5033.2}     # dense MFMA peaks, TFLOP/s (TOPS for int8)
 
+# L2 <-> fabric bytes per launch, averaged over the four launches of a sweep step, from the FETCH_SIZE /
+# WRITE_SIZE counter runs summarised in profiles/bench_fp32_sweep_hbm_traffic.txt (scaled by a 1 GiB copy).
+# Valid only for the kernels those runs profiled; any other selection reports null.
+TRAFFIC_BYTES_PER_LAUNCH = 3189.2e6
+TRAFFIC_KERNELS = ["f32_128x64_w64x32_dma", "f32_64x64_w32x32"]
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -32,6 +38,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-extras", action="store_true", help="skip the per-shape table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (outside the timed region), the known-size "
+                         "kernel that hardware byte counters are scaled by")
     return ap.parse_args()
 
 
@@ -110,6 +119,14 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     # ---------------- headline: the fp32 square sweep
     sweep = [Case("f32", "col", n, n, n, 1.5, 0.5, 2000 + i) for i, n in enumerate(wl.FP32_SQUARES)]
     kernels = [c.kernel() for c in sweep]
@@ -141,7 +158,9 @@ def main():
                    "kernels": sorted(set(k for k, _ in kernels)), "wall_s": round(wall, 3)},
         "pct_of_peak": round(100.0 * tflops / PEAK["f32"], 2),
         "roofline": {"bound": "mfma", "achieved": round(tflops, 3), "peak": PEAK["f32"], "unit": "TFLOP/s",
-                     "frac": round(tflops / PEAK["f32"], 4), "traffic": None,
+                     "frac": round(tflops / PEAK["f32"], 4),
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH if sorted(set(k for k, _ in kernels)) == sorted(TRAFFIC_KERNELS)
+                     else None,
                      "kernel": sorted(set(k for k, _ in kernels)), "launches": launches,
                      "avg_launch_ms": round(ms / launches, 5)},
     }
