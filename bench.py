@@ -10,6 +10,8 @@ The headline value is the throughput of the timed steps in TFLOP/s
     (HIP events on the launch stream) against the fp32 matrix peak,
   * "per_shape": each configuration's own rate (fp32 squares, fp16 squares,
     int8 shapes, the six headline im2row shapes), % of the data type's peak,
+  * "solo_mode": the micro-kernel of each data type's large tile run alone on
+    LDS-resident random operands - the ceiling this machine sustains,
   * "cpu_baseline": the CPU oracle timed on a bounded slice of the 4096^3 case.
 """
 import argparse
@@ -197,6 +199,39 @@ def main():
                 measure("c5 int8", Case("i8", layout, M, N, K, 1, 0, 5000 + i))
             torch.cuda.empty_cache()
         result["per_shape"] = rows
+
+        # ---------------- solo mode: the micro-kernel of each data type's large-problem tile alone
+        # (operands resident in LDS, pseudo-random values), the measured ceiling of that kernel here
+        def solo_rate(dtype, kid):
+            bm, bn, bk, wpc = mg.gemm_kernel_tile(code[dtype], kid)
+            wgs = 256 * max(1, wpc)
+
+            def run(ksteps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record(stream)
+                mg.gemm_solo(code[dtype], kid, wgs, ksteps, 1, stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1)
+
+            run(200)
+            ksteps = int(max(200, min(200000, 2000 * 15.0 / max(run(2000), 1e-3))))   # about 15 ms
+            ms = min(run(ksteps) for _ in range(2))
+            return 2.0 * bm * bn * bk * ksteps * wgs / (ms * 1e-3) / 1e12
+
+        ceilings = {}
+        names = {d: [mg.gemm_kernel_name(code[d], i) for i in range(mg.gemm_kernel_count(code[d]))] for d in code}
+        for dtype in ("f32", "f16", "i8"):
+            big = max((r for r in rows if r["dtype"] == dtype), key=lambda r: r["M"] * r["N"] * r["K"])
+            rate = solo_rate(dtype, names[dtype].index(big["kernel"]))
+            ceilings[dtype] = {"kernel": big["kernel"], "solo_tflops": round(rate, 1),
+                               "pct_peak": round(100.0 * rate / PEAK[dtype], 1)}
+        result["solo_mode"] = ceilings
+        for r in rows:
+            c = ceilings[r["dtype"]]
+            if r["kernel"] == c["kernel"]:
+                r["pct_solo"] = round(100.0 * r["tflops"] / c["solo_tflops"], 1)
 
     # ---------------- the CPU oracle on a bounded slice of the same workload
     if not args.no_cpu:

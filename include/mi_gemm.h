@@ -113,6 +113,25 @@ int gemm_force_kernel(int dtype, int id, int split);
 int gemm_last_kernel_id(void);
 int gemm_last_split(void);
 
+/* Tile of configuration `id`: BM x BN of C per workgroup, BK elements of K per
+ * step, and how many workgroups the kernel is built to keep resident per CU.
+ * Any output pointer may be NULL.  Returns 0, or -1 for an unknown dtype / id. */
+int gemm_kernel_tile(int dtype, int id, int *bm, int *bn, int *bk, int *workgroups_per_cu);
+
+/*
+ * Solo mode (paper Sec. "Solo Mode": the micro-kernel run on its own).  Launches
+ * `workgroups` workgroups of configuration `id`; each fills one LDS stage with
+ * operands (fill = 0: zeros, 1: pseudo-random finite values) and repeats the
+ * fragment reads and MFMAs of one K step `ksteps` times on it - no global
+ * memory traffic, no barriers, no output.  The work is
+ * workgroups * ksteps * 2*BM*BN*BK flop (ops); the caller times it on `stream`
+ * (asynchronous, like the GEMM calls).  The rate reached is the measured
+ * ceiling for that tile on this machine at the clock it sustains under the
+ * load.  Returns 0; -1/-2 unknown dtype/id, -3 workgroups outside [1, 2^20],
+ * -4 negative ksteps, -5 fill not 0 or 1; positive = HIP error code.
+ */
+int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     gemm_kernel_count,
     gemm_kernel_name,
     gemm_force_kernel,
+    gemm_kernel_tile,
+    gemm_solo,
     gemm_last_kernel_id,
     gemm_last_split,
 )

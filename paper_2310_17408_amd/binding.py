@@ -52,6 +52,10 @@ def load():
     lib.gemm_kernel_name.argtypes = [ci, ci]
     lib.gemm_force_kernel.restype = ci
     lib.gemm_force_kernel.argtypes = [ci, ci, ci]
+    lib.gemm_kernel_tile.restype = ci
+    lib.gemm_kernel_tile.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 4
+    lib.gemm_solo.restype = ci
+    lib.gemm_solo.argtypes = [ci, ci, ci, ci, ci, vp]
     lib.gemm_last_kernel_id.restype = ci
     lib.gemm_last_split.restype = ci
     _lib = lib
@@ -121,6 +125,22 @@ def gemm_kernel_name(dtype, kernel_id):
 
 def gemm_force_kernel(dtype, kernel_id=-1, split=0):
     return int(load().gemm_force_kernel(dtype, kernel_id, split))
+
+
+def gemm_kernel_tile(dtype, kernel_id):
+    """(BM, BN, BK, workgroups per CU) of a tile configuration."""
+    out = [ctypes.c_int(0) for _ in range(4)]
+    status = load().gemm_kernel_tile(dtype, kernel_id, *[ctypes.byref(o) for o in out])
+    if status != 0:
+        raise GemmError(status, "unknown dtype or kernel id")
+    return tuple(o.value for o in out)
+
+
+def gemm_solo(dtype, kernel_id, workgroups, ksteps, fill=1, stream=None, check=True):
+    status = load().gemm_solo(dtype, kernel_id, workgroups, ksteps, fill, _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, "gemm_solo: bad argument" if status < 0 else gemm_status_string(status))
+    return status
 
 
 def gemm_last_kernel_id():

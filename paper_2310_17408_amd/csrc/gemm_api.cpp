@@ -239,6 +239,28 @@ int gemm_force_kernel(int dtype, int id, int split)
     return 0;
 }
 
+int gemm_kernel_tile(int dtype, int id, int *bm, int *bn, int *bk, int *workgroups_per_cu)
+{
+    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    if (!ki) return -1;
+    if (bm) *bm = ki->BM;
+    if (bn) *bn = ki->BN;
+    if (bk) *bk = ki->BK;
+    if (workgroups_per_cu) *workgroups_per_cu = ki->min_blocks_per_cu;
+    return 0;
+}
+
+int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *stream)
+{
+    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    if (!ki) return dtype < 0 || dtype > 2 ? -1 : -2;
+    if (workgroups < 1 || workgroups > (1 << 20)) return -3;
+    if (ksteps < 0) return -4;
+    if (fill != 0 && fill != 1) return -5;
+    hipError_t e = ki->solo(workgroups, ksteps, fill, (hipStream_t)stream);
+    return e == hipSuccess ? 0 : (int)e;
+}
+
 int gemm_last_kernel_id(void) { return t_last_id; }
 int gemm_last_split(void) { return t_last_split; }
 

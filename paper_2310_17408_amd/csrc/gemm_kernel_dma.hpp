@@ -114,6 +114,72 @@ __device__ __forceinline__ v4i guarded_chunk(const typename DT::elt *src, int va
     return v;
 }
 
+// The micro-kernel of the direct kernels (loop L6 and the fragment reads that feed it), shared by
+// the GEMM kernel and by the solo-mode benchmark.  A stage holds the A tile (k-rows of BM elements,
+// chunks swizzled by k) followed by the B tile (rows of B_ROWB bytes, chunks swizzled by row).
+template <class T>
+struct DmaMicro {
+    typedef typename T::DT DT;
+    typedef typename DT::accv accv;
+    static constexpr int TM = T::TM, TN = T::TN, ES = T::ES, KCH = T::KCH, A_ROWB = T::A_ROWB, KH = T::KH;
+    // the fragments of one step: per block row / column 16 bytes = KCH consecutive k
+    struct aset { v4i v[TM]; };
+    struct bset { v4i v[TN]; };
+    uint32_t aoff[TM], boff[T::KSTEPS];
+
+    // fragment addresses of this lane inside a stage, for the wave whose tile starts at (wm0, wn0)
+    __device__ __forceinline__ void init(int lane, int wm0, int wn0)
+    {
+        const int frow = lane & 31, fgrp = lane >> 5;
+        // B: row wn0 + 32*j + frow, logical chunk 2*s + fgrp; wn0 and 32*j are multiples of 16,
+        // so the swizzle of the row depends on frow only
+        const int x = (frow / T::B_RP256) % T::B_CPR;
+#pragma unroll
+        for (int s = 0; s < T::KSTEPS; ++s)
+            boff[s] = T::A_BYTES + (wn0 + frow) * T::B_ROWB + (((2 * s + fgrp) ^ x) << 4);
+        // A: the 16-lane group q = lane/16 serves m-half q%2 of the block for k-group q/2 (= fgrp);
+        // inside it, lane t addresses k-row t/LPR and the (t%LPR)-th 8-byte piece of 16 m.
+        const int t = lane & 15, mh = (lane >> 4) & 1;
+        const int kr = t / T::LPR, ml = t % T::LPR;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mbyte = (wm0 + 32 * i + 16 * mh) * ES + 8 * ml;
+            const int ch = (mbyte >> 4) ^ ((kr & T::SWZ_MASK) << T::SWZ_SHIFT);
+            aoff[i] = (KCH * fgrp + kr) * A_ROWB + (ch << 4) + (mbyte & 15);
+        }
+    }
+
+    // LDS reads of fragment step s (2*KCH consecutive k) of the stage at `stage`
+    __device__ __forceinline__ void load(const unsigned char *stage, int s, aset &xa, bset &xb) const
+    {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            // two transposing reads give this lane KCH consecutive k of its m
+            const unsigned char *q0 = stage + aoff[i] + (2 * KCH * s) * A_ROWB;
+            const unsigned char *q1 = q0 + KH * A_ROWB;
+            if constexpr (ES == 2) {
+                v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
+                v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
+                xa.v[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
+                v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
+                xa.v[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) xb.v[j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
+    }
+
+    static __device__ __forceinline__ void mma(aset &xa, bset &xb, accv (&acc)[TM][TN])
+    {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) Mma<DT>::run(xb.v[j], xa.v[i], acc[i][j]);
+    }
+};
+
 template <class T>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p)
 {
@@ -121,8 +187,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     typedef typename DT::elt elt;
     typedef typename DT::accv accv;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NW = T::NW, ES = T::ES, KCH = T::KCH;
-    constexpr int TM = T::TM, TN = T::TN, A_ROWB = T::A_ROWB, A_CPR = T::A_CPR;
-    constexpr int LPR = T::LPR, KH = T::KH;
+    constexpr int TM = T::TM, TN = T::TN, A_CPR = T::A_CPR;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(MIG_LDS unsigned char *)smem;
@@ -222,29 +287,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
         stage_guarded(kt, buf, tile_fast_a && kfull, tile_fast_b && kfull);
     };
 
-    // ---- fragment addresses of this lane inside a stage
-    const int frow = lane & 31, fgrp = lane >> 5;
-    // B: row wn0 + 32*j + frow, logical chunk 2*s + fgrp
-    uint32_t boff[T::KSTEPS];
-    {
-        const int x = (frow / T::B_RP256) % T::B_CPR;   // swizzle of the row: wn0 and 32*j are multiples of 16
-#pragma unroll
-        for (int s = 0; s < T::KSTEPS; ++s)
-            boff[s] = T::A_BYTES + (wn0 + frow) * T::B_ROWB + (((2 * s + fgrp) ^ x) << 4);
-    }
-    // A: the 16-lane group q = lane/16 serves m-half q%2 of the block for k-group q/2 (= fgrp);
-    // inside it, lane t addresses k-row t/LPR and the (t%LPR)-th 8-byte piece of 16 m.
-    uint32_t aoff[TM];
-    {
-        const int t = lane & 15, mh = (lane >> 4) & 1;
-        const int kr = t / LPR, ml = t % LPR;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mbyte = (wm0 + 32 * i + 16 * mh) * ES + 8 * ml;
-            const int ch = (mbyte >> 4) ^ ((kr & T::SWZ_MASK) << T::SWZ_SHIFT);
-            aoff[i] = (KCH * fgrp + kr) * A_ROWB + (ch << 4) + (mbyte & 15);
-        }
-    }
+    DmaMicro<T> micro;
+    micro.init(lane, wm0, wn0);
 
     accv acc[TM][TN];
 #pragma unroll
@@ -257,32 +301,13 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     // ---- the micro-kernel: KSTEPS fragment steps of 2*KCH consecutive k per stage.  Fragments are
     // double buffered in registers: while the MFMAs of one step run, the LDS reads of the next are
     // in flight, also across the barrier that ends a K step.
-    v4i fa[2][TM], fb[2][TN];
-    auto load_frags = [&](int buf, int s, v4i (&xa)[TM], v4i (&xb)[TN]) {
-        const unsigned char *stage = smem + buf * T::STAGE;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            // two transposing reads give this lane KCH consecutive k of its m
-            const unsigned char *q0 = stage + aoff[i] + (2 * KCH * s) * A_ROWB;
-            const unsigned char *q1 = q0 + KH * A_ROWB;
-            if constexpr (ES == 2) {
-                v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
-                v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
-                xa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
-            } else {
-                v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
-                v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
-                xa[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) xb[j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
+    typename DmaMicro<T>::aset fa[2];
+    typename DmaMicro<T>::bset fb[2];
+    auto load_frags = [&](int buf, int s, typename DmaMicro<T>::aset &xa, typename DmaMicro<T>::bset &xb) {
+        micro.load(smem + buf * T::STAGE, s, xa, xb);
     };
-    auto mma_step = [&](v4i (&xa)[TM], v4i (&xb)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) Mma<DT>::run(xb[j], xa[i], acc[i][j]);
+    auto mma_step = [&](typename DmaMicro<T>::aset &xa, typename DmaMicro<T>::bset &xb) {
+        DmaMicro<T>::mma(xa, xb, acc);
     };
     // all but the last step of the stage `buf`; on entry the fragments of its step 0 are in set 0
     auto steps_but_last = [&](int buf) {

@@ -84,6 +84,60 @@ __device__ __forceinline__ void wait_transfers_upto(int allowed)
     else wait_transfers<0>();
 }
 
+// The fp32 micro-kernel of the direct kernels and the fragment reads that feed it, shared by the
+// GEMM kernel and by the solo-mode benchmark.  A fragment step is 8 consecutive k = 4 MFMAs per block.
+template <class T>
+struct Dma32Micro {
+    typedef v16f accv;
+    static constexpr int TM = T::TM, TN = T::TN, A_ROWB = T::A_ROWB, B_ROWB = T::B_ROWB;
+    // the fragments of one step: for each of 4 MFMAs the TM floats of m this lane owns, and per
+    // block column 4 consecutive k of its row n
+    struct aset { float v[4][TM]; };
+    struct bset { v4f v[TN]; };
+    uint32_t aoff, boff[T::KSTEPS];
+
+    __device__ __forceinline__ void init(int lane, int wm0, int wn0)
+    {
+        const int frow = lane & 31, fgrp = lane >> 5;
+        const int x = (frow / T::B_RP256) % T::B_CPR;
+#pragma unroll
+        for (int s = 0; s < T::KSTEPS; ++s)
+            boff[s] = T::A_BYTES + (wn0 + frow) * B_ROWB + (((2 * s + fgrp) ^ x) << 4);
+        // A: k-row 8*s + 4*fgrp + t, floats wm0 + TM*frow ... + TM-1
+        aoff = (4 * fgrp) * A_ROWB + (wm0 + TM * frow) * 4;
+    }
+
+    __device__ __forceinline__ void load(const unsigned char *stage, int s, aset &xa, bset &xb) const
+    {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const unsigned char *q = stage + aoff + (8 * s + t) * A_ROWB;
+            if constexpr (TM == 1) {
+                xa.v[t][0] = *(const float *)q;
+            } else if constexpr (TM == 2) {
+                v2f v = *(const v2f *)q;
+                xa.v[t][0] = v[0]; xa.v[t][1] = v[1];
+            } else {
+                v4f v = *(const v4f *)q;
+                xa.v[t][0] = v[0]; xa.v[t][1] = v[1]; xa.v[t][2] = v[2]; xa.v[t][3] = v[3];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) xb.v[j] = *(const v4f *)(stage + boff[s] + j * 32 * B_ROWB);
+    }
+
+    static __device__ __forceinline__ void mma(aset &xa, bset &xb, accv (&acc)[TM][TN])
+    {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xb.v[j][t], xa.v[t][i], acc[i][j], 0, 0, 0);
+    }
+};
+
 template <class T>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params p)
 {
@@ -198,17 +252,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
         stage_b(kt, buf, in_b && kfull);
     };
 
-    // ---- fragment addresses of this lane inside a stage
     const int frow = lane & 31, fgrp = lane >> 5;
-    uint32_t boff[T::KSTEPS];
-    {
-        const int x = (frow / T::B_RP256) % T::B_CPR;
-#pragma unroll
-        for (int s = 0; s < T::KSTEPS; ++s)
-            boff[s] = T::A_BYTES + (wn0 + frow) * B_ROWB + (((2 * s + fgrp) ^ x) << 4);
-    }
-    // A: k-row 8*s + 4*fgrp + t, floats wm0 + TM*frow ... + TM-1
-    const uint32_t aoff = (4 * fgrp) * A_ROWB + (wm0 + TM * frow) * 4;
+    Dma32Micro<T> micro;
+    micro.init(lane, wm0, wn0);
 
     v16f acc[TM][TN];
 #pragma unroll
@@ -218,35 +264,14 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    // ---- the micro-kernel: a fragment step is 8 consecutive k = 4 MFMAs per block
-    float fa[2][4][TM];
-    v4f fb[2][TN];
-    auto load_frags = [&](int buf, int s, float (&xa)[4][TM], v4f (&xb)[TN]) {
-        const unsigned char *stage = smem + buf * T::STAGE;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const unsigned char *q = stage + aoff + (8 * s + t) * A_ROWB;
-            if constexpr (TM == 1) {
-                xa[t][0] = *(const float *)q;
-            } else if constexpr (TM == 2) {
-                v2f v = *(const v2f *)q;
-                xa[t][0] = v[0]; xa[t][1] = v[1];
-            } else {
-                v4f v = *(const v4f *)q;
-                xa[t][0] = v[0]; xa[t][1] = v[1]; xa[t][2] = v[2]; xa[t][3] = v[3];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) xb[j] = *(const v4f *)(stage + boff[s] + j * 32 * B_ROWB);
+    // ---- the micro-kernel, fragments double buffered in registers
+    typename Dma32Micro<T>::aset fa[2];
+    typename Dma32Micro<T>::bset fb[2];
+    auto load_frags = [&](int buf, int s, typename Dma32Micro<T>::aset &xa, typename Dma32Micro<T>::bset &xb) {
+        micro.load(smem + buf * T::STAGE, s, xa, xb);
     };
-    auto mma_step = [&](float (&xa)[4][TM], v4f (&xb)[TN]) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xb[j][t], xa[t][i], acc[i][j], 0, 0, 0);
+    auto mma_step = [&](typename Dma32Micro<T>::aset &xa, typename Dma32Micro<T>::bset &xb) {
+        Dma32Micro<T>::mma(xa, xb, acc);
     };
     auto steps_but_last = [&](int buf) {
 #pragma unroll

@@ -36,6 +36,10 @@ struct KernelInfo {
     // one with the lowest prio.  prio 0: only by explicit request.
     int prio;
     int min_tiles;
+    // Solo mode: `workgroups` workgroups repeat the micro-kernel of one K step `ksteps` times on
+    // operands resident in LDS (fill 0: zeros, 1: pseudo-random finite values).
+    hipError_t (*solo)(int workgroups, int ksteps, int fill, hipStream_t);
+    int min_blocks_per_cu;   // workgroups per CU the kernel is built to co-reside with
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8

@@ -4,9 +4,39 @@
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
+#include "gemm_solo.hpp"
 #include "gemm_table.h"
 
 namespace mig {
+
+template <class T, class K>
+static hipError_t launch_solo(K kernel, int workgroups, int ksteps, int fill, hipStream_t stream)
+{
+    static bool attr_done[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                T::STAGE);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)workgroups), dim3(T::NT), T::STAGE, stream, ksteps, fill);
+    return hipGetLastError();
+}
+template <class T>
+static hipError_t solo_staged(int wg, int ks, int fill, hipStream_t st) { return launch_solo<T>(&solo_kernel<T>, wg, ks, fill, st); }
+template <class T>
+static hipError_t solo_dma(int wg, int ks, int fill, hipStream_t st)
+{
+    return launch_solo<T>(&solo_kernel_direct<T, DmaMicro<T>>, wg, ks, fill, st);
+}
+template <class T>
+static hipError_t solo_dma32(int wg, int ks, int fill, hipStream_t st)
+{
+    return launch_solo<T>(&solo_kernel_direct<T, Dma32Micro<T>>, wg, ks, fill, st);
+}
 
 template <class T>
 static hipError_t launch_tile(const Params &p, hipStream_t stream)
@@ -47,7 +77,7 @@ static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
 template <class T>
 static constexpr KernelInfo info_dma(const char *name, int prio, int min_tiles)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, min_tiles};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, min_tiles, &solo_dma<T>, T::MINB};
 }
 
 template <class T>
@@ -71,13 +101,13 @@ static hipError_t launch_tile_dma32(const Params &p, hipStream_t stream)
 template <class T>
 static constexpr KernelInfo info_dma32(const char *name, int prio, int min_tiles)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, min_tiles};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, min_tiles, &solo_dma32<T>, T::MINB};
 }
 
 template <class T>
 static constexpr KernelInfo info(const char *name, int prio, int min_tiles)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, min_tiles};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, min_tiles, &solo_staged<T>, T::MINB};
 }
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU

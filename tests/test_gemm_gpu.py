@@ -239,3 +239,18 @@ def test_other_table_shapes_f32():
     for idx, (M, N, K) in enumerate([wl.VGG16_IM2ROW[0], wl.RESNET50_IM2ROW[1], wl.RESNET50_IM2ROW[12],
                                      wl.RESNET50_IM2ROW[17]]):
         check_case("f32", "col", M, N, K, 1.0, 0.0, seed=4100 + idx)
+
+
+# ------------------------------------------------------------ solo mode
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_solo_mode_runs_every_kernel(dtype):
+    """The micro-kernel benchmark launches and completes for every tile configuration."""
+    for kid in _kernels(dtype):
+        bm, bn, bk, wpc = mg.gemm_kernel_tile(DT[dtype], kid)
+        assert bm % 32 == 0 and bn % 32 == 0 and bk > 0 and wpc >= 1
+        for fill in (0, 1):
+            assert mg.gemm_solo(DT[dtype], kid, 64, 50, fill) == 0
+    torch.cuda.synchronize()
+    assert mg.gemm_solo(DT[dtype], 0, 0, 10, 1, check=False) == -3
+    assert mg.gemm_solo(DT[dtype], 99, 8, 10, 1, check=False) == -2
+    assert mg.gemm_solo(DT[dtype], 0, 8, 10, 2, check=False) == -5
