@@ -113,6 +113,14 @@ int gemm_force_kernel(int dtype, int id, int split);
 int gemm_last_kernel_id(void);
 int gemm_last_split(void);
 
+/* What a call with these arguments would launch (pure host computation, nothing
+ * runs): the tile configuration and the K split chosen by the selector - or the
+ * forced ones - for a workspace of `workspace_bytes`.  Either output pointer may
+ * be NULL.  Returns 0, or -1 unknown dtype, -2 unknown layout, -3/-4/-5 M/N/K
+ * not positive or too large. */
+int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int *kernel_id,
+                int *split);
+
 /* Tile of configuration `id`: BM x BN of C per workgroup, BK elements of K per
  * step, and how many workgroups the kernel is built to keep resident per CU.
  * Any output pointer may be NULL.  Returns 0, or -1 for an unknown dtype / id. */

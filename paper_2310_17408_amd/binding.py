@@ -54,6 +54,8 @@ def load():
     lib.gemm_force_kernel.argtypes = [ci, ci, ci]
     lib.gemm_kernel_tile.restype = ci
     lib.gemm_kernel_tile.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 4
+    lib.gemm_select.restype = ci
+    lib.gemm_select.argtypes = [ci, ci, i64, i64, i64, sz, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.gemm_solo.restype = ci
     lib.gemm_solo.argtypes = [ci, ci, ci, ci, ci, vp]
     lib.gemm_last_kernel_id.restype = ci
@@ -134,6 +136,15 @@ def gemm_kernel_tile(dtype, kernel_id):
     if status != 0:
         raise GemmError(status, "unknown dtype or kernel id")
     return tuple(o.value for o in out)
+
+
+def gemm_select(dtype, layout, M, N, K, workspace_bytes):
+    """(kernel id, split) a call with these arguments would launch; nothing runs."""
+    kid, split = ctypes.c_int(-1), ctypes.c_int(0)
+    status = load().gemm_select(dtype, layout, M, N, K, workspace_bytes, ctypes.byref(kid), ctypes.byref(split))
+    if status != 0:
+        raise GemmError(status, "gemm_select: bad argument")
+    return kid.value, split.value
 
 
 def gemm_solo(dtype, kernel_id, workgroups, ksteps, fill=1, stream=None, check=True):

@@ -26,53 +26,98 @@ int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // What the selector settles on for one canonical problem.
 struct Choice { int id; int split; int ktiles_per_split; };
 
-// K split for a given tile: only when the grid would leave most CUs idle and K
-// is long enough to give every slice at least two steps.
-int auto_split(int64_t tiles, int64_t ktiles)
+// ---------------------------------------------------------------------------
+// Tile and split selection by a small analytical model: the analogue of the
+// paper's choice of the micro-kernel size that matches the problem (Secs. "Edge
+// Cases", "Squared Matrices") and of the blocking-parameter model it cites for
+// the packed buffers.  For every candidate (tile configuration, K split) the
+// predicted time is
+//     launch + max(rounds * steps * step_time, staged_bytes / staging_bandwidth) + reduce(split)
+// where rounds  = ceil(tiles*split / (CUs * workgroups per CU)),
+//       steps   = ceil(K steps / split),
+//       step_time = max(co-resident workgroups * MFMA time of one K step, latency floor of a step),
+//       reduce  = second launch + split partial tiles written and read back.
+// The constants are measured on MI355X: sustained MFMA rate per data type (solo mode on random
+// data), 14 TB/s from L2 into LDS for GEMM-like tile streams, the time of a K step when a
+// workgroup is alone on its CU (per configuration), 2 TB/s for the partial-tile round trip, 4 us per launch.
+// ---------------------------------------------------------------------------
+constexpr double kSustainedTflops[3] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61};
+constexpr double kStagingBytesPerUs = 14.0e6;
+constexpr double kStepFloorUs = 0.75;
+constexpr double kReduceBytesPerUs = 2.0e6;
+constexpr double kLaunchUs = 4.0;
+constexpr int kMaxAutoSplit = 16;
+
+double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split)
 {
-    if (tiles >= NUM_CU * 3 / 4 || ktiles < 4) return 1;
-    int64_t s = ceil_div(NUM_CU, tiles);
-    if (s > ktiles / 2) s = ktiles / 2;
-    if (s > MAX_SPLIT) s = MAX_SPLIT;
-    return s < 1 ? 1 : (int)s;
+    static const int es[3] = {4, 2, 1};
+    const double tiles = (double)(ceil_div(M, ki->BM) * ceil_div(N, ki->BN));
+    const double ktiles = (double)ceil_div(K, ki->BK);
+    const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
+    const double wgs = tiles * split;
+    // workgroups are dealt to free slots as they come, so beyond one round the count is fractional
+    double rounds = wgs / ((double)NUM_CU * occ);
+    rounds = rounds <= 1.0 ? 1.0 : (double)ceil_div((int64_t)(rounds * 4.0), 1) / 4.0;
+    double resident = (double)ceil_div((int64_t)wgs, NUM_CU);        // workgroups sharing a CU
+    if (resident > occ) resident = occ;
+    const double steps = (double)ceil_div((int64_t)ktiles, split);
+    const double eff = (ki->eff_pct > 0 ? ki->eff_pct : 100) / 100.0;
+    const double mfma_step = 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
+    double step = resident * mfma_step;
+    const double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
+    if (step < floor_us) step = floor_us;
+    double main_us = rounds * steps * step;
+    const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
+    if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
+    double reduce_us = 0.0;
+    if (split > 1) reduce_us = kLaunchUs + (double)split * (double)M * (double)N * 8.0 / kReduceBytesPerUs;
+    return kLaunchUs + main_us + reduce_us;
 }
 
-// Tile selection (the analogue of choosing the micro-kernel size that matches
-// the problem, paper Secs. "Edge Cases" and "Squared Matrices"): configurations
-// are tried in order of falling priority and the first one that yields enough
-// tiles to keep the 256 CUs busy wins; small problems fall through to the
-// smallest tile, which is then helped by splitting K.
-int auto_kernel(int dtype, int64_t M, int64_t N)
+// Best split for one configuration (used directly when the configuration is forced).
+int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split)
+{
+    const int64_t ktiles = ceil_div(K, ki->BK);
+    int best = 1;
+    double best_us = predict_us(dtype, ki, M, N, K, 1);
+    for (int s = 2; s <= kMaxAutoSplit && s <= max_split && 2 * s <= ktiles; ++s) {
+        const double t = predict_us(dtype, ki, M, N, K, s);
+        if (t < best_us * 0.97) { best_us = t; best = s; }     // a split must pay for itself clearly
+    }
+    return best;
+}
+
+// Best (configuration, split) over the configurations open to automatic selection (prio > 0).
+int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t max_split_bytes_per_mn)
 {
     const int n = kernel_count(dtype);
-    int best = -1, best_prio = 0;
-    int fallback = 0, fallback_prio = INT_MAX;
+    int best = -1;
+    double best_us = 0.0;
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
         if (ki->prio <= 0) continue;
-        const int64_t tiles = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
-        if (ki->prio < fallback_prio) { fallback_prio = ki->prio; fallback = id; }
-        if (tiles >= ki->min_tiles && ki->prio > best_prio) { best_prio = ki->prio; best = id; }
+        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn);
+        const double t = predict_us(dtype, ki, M, N, K, s);
+        if (best < 0 || t < best_us) { best = id; best_us = t; }
     }
-    return best >= 0 ? best : fallback;
+    return best < 0 ? 0 : best;
 }
 
 Choice choose(int dtype, int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool have_ws)
 {
     Choice c;
     const Forced f = g_forced[dtype];
-    c.id = (f.id >= 0 && f.id < kernel_count(dtype)) ? f.id : auto_kernel(dtype, M, N);
+    // how many partial tiles the workspace can hold
+    const unsigned __int128 per = (unsigned __int128)M * (unsigned __int128)N * 4u;
+    int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
+    if (fit > MAX_SPLIT) fit = MAX_SPLIT;
+    if (fit < 1) fit = 1;
+    c.id = (f.id >= 0 && f.id < kernel_count(dtype)) ? f.id : auto_kernel(dtype, M, N, K, fit);
     const KernelInfo *ki = kernel_info(dtype, c.id);
-    const int64_t tiles = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
     const int64_t ktiles = ceil_div(K, ki->BK);
-    int64_t s = f.split >= 1 ? f.split : auto_split(tiles, ktiles);
+    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit);
     if (s > ktiles) s = ktiles;
-    if (s > MAX_SPLIT) s = MAX_SPLIT;
-    if (s > 1) {
-        const unsigned __int128 per = (unsigned __int128)M * (unsigned __int128)N * 4u;
-        const int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
-        if (s > fit) s = fit;
-    }
+    if (s > fit) s = fit;
     if (s < 1) s = 1;
     c.ktiles_per_split = (int)ceil_div(ktiles, s);
     c.split = (int)ceil_div(ktiles, c.ktiles_per_split);   // every slice gets at least one step
@@ -191,14 +236,12 @@ size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
 {
     if (dtype < 0 || dtype > 2 || M <= 0 || N <= 0 || K <= 0) return 0;
     if (M > INT_MAX || N > INT_MAX || K > INT_MAX) return 0;
-    // the largest split any tile of this dtype would be given by the selector
+    // the largest split the model would give any configuration, in either orientation (a
+    // row-major call runs the transposed problem)
     int64_t smax = 1;
     for (int id = 0; id < kernel_count(dtype); ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        // either orientation: a row-major call runs the transposed problem
-        const int64_t t1 = ceil_div(M, ki->BM) * ceil_div(N, ki->BN);
-        const int64_t t2 = ceil_div(N, ki->BM) * ceil_div(M, ki->BN);
-        const int64_t s1 = auto_split(t1, ceil_div(K, ki->BK)), s2 = auto_split(t2, ceil_div(K, ki->BK));
+        const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT), s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT);
         if (s1 > smax) smax = s1;
         if (s2 > smax) smax = s2;
     }
@@ -247,6 +290,21 @@ int gemm_kernel_tile(int dtype, int id, int *bm, int *bn, int *bk, int *workgrou
     if (bn) *bn = ki->BN;
     if (bk) *bk = ki->BK;
     if (workgroups_per_cu) *workgroups_per_cu = ki->min_blocks_per_cu;
+    return 0;
+}
+
+int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int *kernel_id,
+                int *split)
+{
+    if (dtype < 0 || dtype > 2) return -1;
+    if (layout != MI_GEMM_COL_MAJOR && layout != MI_GEMM_ROW_MAJOR) return -2;
+    if (M <= 0 || M > INT_MAX) return -3;
+    if (N <= 0 || N > INT_MAX) return -4;
+    if (K <= 0 || K > INT_MAX) return -5;
+    const bool col = (layout == MI_GEMM_COL_MAJOR);
+    const Choice ch = choose(dtype, col ? M : N, col ? N : M, K, workspace_bytes, workspace_bytes > 0);
+    if (kernel_id) *kernel_id = ch.id;
+    if (split) *split = ch.split;
     return 0;
 }
 

@@ -47,7 +47,7 @@ __device__ __forceinline__ void solo_finish(accv (&acc)[TM][TN])
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) r += (float)acc[i][j][0];
-    if (r == 12345.678f) g_solo_sink = 1;
+    if (r == 1234567.0f) g_solo_sink = 1;   // integer-valued: reachable for int accumulators too, so nothing is dead code
 }
 
 // staged kernels (gemm_kernel.hpp)

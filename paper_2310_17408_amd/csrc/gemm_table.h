@@ -31,11 +31,12 @@ struct KernelInfo {
     int threads;
     int lds_bytes;
     hipError_t (*launch)(const Params &, hipStream_t);
-    // Automatic selection: among the configurations with prio > 0, in order of falling prio, the
-    // first one whose tile count for the problem reaches min_tiles is taken; if none does, the
-    // one with the lowest prio.  prio 0: only by explicit request.
+    // prio > 0: open to automatic selection (the host's timing model picks among these);
+    // prio 0: only by explicit request.  eff_pct: the share of its micro-kernel's solo-mode rate
+    // that the whole kernel reaches on large problems (measured), used by the timing model.
     int prio;
-    int min_tiles;
+    int eff_pct;
+    int step_floor_ns;       // time of one K step when the workgroup has its CU to itself (latency-bound)
     // Solo mode: `workgroups` workgroups repeat the micro-kernel of one K step `ksteps` times on
     // operands resident in LDS (fill 0: zeros, 1: pseudo-random finite values).
     hipError_t (*solo)(int workgroups, int ksteps, int fill, hipStream_t);

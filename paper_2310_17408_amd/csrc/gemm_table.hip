@@ -75,9 +75,9 @@ static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
 }
 
 template <class T>
-static constexpr KernelInfo info_dma(const char *name, int prio, int min_tiles)
+static constexpr KernelInfo info_dma(const char *name, int prio, int eff_pct, int floor_ns)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, min_tiles, &solo_dma<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, eff_pct, floor_ns, &solo_dma<T>, T::MINB};
 }
 
 template <class T>
@@ -99,15 +99,15 @@ static hipError_t launch_tile_dma32(const Params &p, hipStream_t stream)
 }
 
 template <class T>
-static constexpr KernelInfo info_dma32(const char *name, int prio, int min_tiles)
+static constexpr KernelInfo info_dma32(const char *name, int prio, int eff_pct, int floor_ns)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, min_tiles, &solo_dma32<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, eff_pct, floor_ns, &solo_dma32<T>, T::MINB};
 }
 
 template <class T>
-static constexpr KernelInfo info(const char *name, int prio, int min_tiles)
+static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, min_tiles, &solo_staged<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, &solo_staged<T>, T::MINB};
 }
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU
@@ -122,28 +122,29 @@ typedef Tile<I8, 256, 256, 2, 2, 8, 1> I8_256x256;
 typedef Tile<I8, 128, 128, 2, 2, 4, 2> I8_128x128;
 typedef Tile<I8, 64, 64, 2, 2, 4, 2> I8_64x64;
 
-// name, priority in the automatic selection, fewest tiles for which it is taken (256 CUs)
+// name, open to automatic selection (> 0), % of the solo-mode rate reached on large problems,
+// ns per K step of a workgroup that is alone on its CU
 static const KernelInfo k_f32[] = {
-    info<F32_128x128>("f32_128x128_w64x64", 0, 0),
-    info<F32_256x128>("f32_256x128_w64x64", 0, 0),
-    info<F32_64x64>("f32_64x64_w32x32", 1, 0),
-    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 0),
-    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 3, 512),
-    info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 0),
+    info<F32_128x128>("f32_128x128_w64x64", 0, 80, 2200),
+    info<F32_256x128>("f32_256x128_w64x64", 0, 82, 3600),
+    info<F32_64x64>("f32_64x64_w32x32", 1, 74, 780),
+    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 70, 900),
+    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 1, 90, 1400),
+    info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 86, 2000),
 };
 static const KernelInfo k_f16[] = {
-    info<F16_256x256>("f16_256x256_w128x128", 0, 0),
-    info<F16_128x128>("f16_128x128_w64x64", 0, 0),
-    info<F16_64x64>("f16_64x64_w32x32", 1, 0),
-    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 2, 256),
-    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 3, 256),
+    info<F16_256x256>("f16_256x256_w128x128", 0, 50, 2500),
+    info<F16_128x128>("f16_128x128_w64x64", 0, 47, 1700),
+    info<F16_64x64>("f16_64x64_w32x32", 1, 40, 600),
+    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 1, 72, 880),
+    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 1, 82, 1800),
 };
 static const KernelInfo k_i8[] = {
-    info<I8_256x256>("i8_256x256_w128x128", 0, 0),
-    info<I8_128x128>("i8_128x128_w64x64", 0, 0),
-    info<I8_64x64>("i8_64x64_w32x32", 1, 0),
-    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 2, 256),
-    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 3, 256),
+    info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500),
+    info<I8_128x128>("i8_128x128_w64x64", 0, 47, 800),
+    info<I8_64x64>("i8_64x64_w32x32", 1, 30, 600),
+    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 1, 62, 880),
+    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 1, 75, 1800),
 };
 
 int kernel_count(int dtype)

@@ -234,6 +234,13 @@ def test_int8_ragged_shapes(layout):
     check_case("i8", layout, 1000, 999, 1001, 2, -1, seed=5010)
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_every_im2row_table_shape_f32(layout):
+    """All 20 ResNet50 v1.5 and 9 VGG16 GEMMs of the paper's two tables, automatic selection."""
+    for idx, (M, N, K) in enumerate(wl.RESNET50_IM2ROW + wl.VGG16_IM2ROW):
+        check_case("f32", layout, M, N, K, 1.0, 0.0, seed=4200 + idx)
+
+
 def test_other_table_shapes_f32():
     """A few of the remaining rows of the two im2row tables (tiny K, skinny M, wide N)."""
     for idx, (M, N, K) in enumerate([wl.VGG16_IM2ROW[0], wl.RESNET50_IM2ROW[1], wl.RESNET50_IM2ROW[12],
