@@ -58,7 +58,8 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
     // workgroups are dealt to free slots as they come, so beyond one round the count is fractional
     double rounds = wgs / ((double)NUM_CU * occ);
     rounds = rounds <= 1.0 ? 1.0 : (double)ceil_div((int64_t)(rounds * 4.0), 1) / 4.0;
-    double resident = (double)ceil_div((int64_t)wgs, NUM_CU);        // workgroups sharing a CU
+    double resident = wgs / NUM_CU;                                  // workgroups sharing a CU, on average
+    if (resident < 1.0) resident = 1.0;
     if (resident > occ) resident = occ;
     const double steps = (double)ceil_div((int64_t)ktiles, split);
     const double eff = (ki->eff_pct > 0 ? ki->eff_pct : 100) / 100.0;
@@ -71,7 +72,7 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
     if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
     double reduce_us = 0.0;
     if (split > 1) reduce_us = kLaunchUs + (double)split * (double)M * (double)N * 8.0 / kReduceBytesPerUs;
-    return kLaunchUs + main_us + reduce_us;
+    return kLaunchUs + ki->setup_ns * 1e-3 + main_us + reduce_us;
 }
 
 // Best split for one configuration (used directly when the configuration is forced).

@@ -23,6 +23,7 @@
 // before the first MFMA.
 #pragma once
 #include "gemm_kernel_dma.hpp"
+#include <type_traits>
 
 namespace mig {
 
@@ -290,6 +291,69 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
         nfast = p.K / BK - kt_begin;
         nfast = nfast < 0 ? 0 : (nfast > nkt ? nkt : nfast);
     }
+    // Direct staging of one full K step with everything a lane or wave needs precomputed: per-wave
+    // base pointers that advance by a constant per step, per-lane offsets that never change.  The
+    // transfer width of each operand (16 or 4 bytes per lane) is a compile-time choice here, so the
+    // hot loop below carries no branches.
+    const unsigned char *a_wave = (const unsigned char *)(A + (int64_t)(wave * T::A_R4) * p.lda + m0);
+    const unsigned char *b_wave = (const unsigned char *)(B + (int64_t)(n0 + wave * T::B_R4) * p.ldb);
+    const int64_t a_step = (int64_t)BK * p.lda * 4, b_step = (int64_t)BK * 4;
+    const int64_t a_blk = (int64_t)NW * T::A_R4 * p.lda * 4, b_blk = (int64_t)NW * T::B_R4 * p.ldb * 4;
+    int64_t a_q[4];          // 4-byte path of A: quarter q of a block starts this many bytes after the block
+    uint32_t b_q[4];         // 4-byte path of B: this lane's byte offset from the block's first row, quarter q
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        a_q[q] = ((int64_t)((q * 256) / A_ROWB) * p.lda + ((q * 256) % A_ROWB) / 4) * 4;
+        const int dw = q * 64 + lane;
+        const int rin = dw / (B_ROWB / 4), pos = dw % (B_ROWB / 4);
+        const int ch = (pos >> 2) ^ (((wave * T::B_R4 + rin) / T::B_RP256) % T::B_CPR);
+        b_q[q] = (uint32_t)(((int64_t)rin * p.ldb + ch * 4 + (pos & 3)) * 4);
+    }
+    auto stage_direct = [&](auto a16c, auto b16c, int kt, int buf) {
+        const unsigned char *ab = a_wave + (int64_t)kt * a_step;
+        const unsigned char *bb = b_wave + (int64_t)kt * b_step;
+        const uint32_t la = lds_base + buf * T::STAGE + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < T::A_J; ++j) {
+            if (T::A_BLK % NW != 0 && wave + NW * j >= T::A_BLK) break;
+            if constexpr (decltype(a16c)::value) {
+                lds_dma16(ab + j * a_blk, a_off16, la + j * NW * 1024);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    lds_dma4(ab + j * a_blk + a_q[q], (uint32_t)lane * 4, la + j * NW * 1024 + q * 256);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < T::B_J; ++j) {
+            if (T::B_BLK % NW != 0 && wave + NW * j >= T::B_BLK) break;
+            if constexpr (decltype(b16c)::value) {
+                lds_dma16(bb + j * b_blk, b_off16, la + T::A_BYTES + j * NW * 1024);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    lds_dma4(bb + j * b_blk, b_q[q], la + T::A_BYTES + j * NW * 1024 + q * 256);
+            }
+        }
+    };
+
+    int buf = 0, i = 0;
+    // hot loop: runs while the step it stages (i + NS) and all steps in flight are direct
+    auto hot_loop = [&](auto a16c, auto b16c) {
+        for (; i + NS < nfast; ++i) {
+            const int nxt = (buf + 1 == NS) ? 0 : buf + 1;
+            steps_but_last(buf);
+            wait_transfers_upto((NS - 2) * my_blocks);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            stage_direct(a16c, b16c, kt_begin + i + NS, buf);
+            load_frags(nxt, 0, fa[0], fb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_step(fa[LAST], fb[LAST]);
+            buf = nxt;
+        }
+    };
+
     if (nkt > 0) {
 #pragma unroll
         for (int t = 0; t < NS; ++t)
@@ -302,8 +366,13 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         load_frags(0, 0, fa[0], fb[0]);
-        int buf = 0;
-        for (int i = 0; i < nkt; ++i) {
+        typedef std::integral_constant<bool, true> yes;
+        typedef std::integral_constant<bool, false> no;
+        if (a16 && b16) hot_loop(yes(), yes());
+        else if (a16) hot_loop(yes(), no());
+        else if (b16) hot_loop(no(), yes());
+        else hot_loop(no(), no());
+        for (; i < nkt; ++i) {
             const int nxt = (buf + 1 == NS) ? 0 : buf + 1;
             steps_but_last(buf);
             if (i + 1 < nkt) {

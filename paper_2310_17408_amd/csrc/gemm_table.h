@@ -37,6 +37,7 @@ struct KernelInfo {
     int prio;
     int eff_pct;
     int step_floor_ns;       // time of one K step when the workgroup has its CU to itself (latency-bound)
+    int setup_ns;            // fixed cost per launch beyond the launch itself (prologue of the kernel)
     // Solo mode: `workgroups` workgroups repeat the micro-kernel of one K step `ksteps` times on
     // operands resident in LDS (fill 0: zeros, 1: pseudo-random finite values).
     hipError_t (*solo)(int workgroups, int ksteps, int fill, hipStream_t);

@@ -75,9 +75,9 @@ static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
 }
 
 template <class T>
-static constexpr KernelInfo info_dma(const char *name, int prio, int eff_pct, int floor_ns)
+static constexpr KernelInfo info_dma(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, eff_pct, floor_ns, &solo_dma<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, eff_pct, floor_ns, setup_ns, &solo_dma<T>, T::MINB};
 }
 
 template <class T>
@@ -99,15 +99,15 @@ static hipError_t launch_tile_dma32(const Params &p, hipStream_t stream)
 }
 
 template <class T>
-static constexpr KernelInfo info_dma32(const char *name, int prio, int eff_pct, int floor_ns)
+static constexpr KernelInfo info_dma32(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, eff_pct, floor_ns, &solo_dma32<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, eff_pct, floor_ns, setup_ns, &solo_dma32<T>, T::MINB};
 }
 
 template <class T>
-static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns)
+static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, &solo_staged<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, setup_ns, &solo_staged<T>, T::MINB};
 }
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU
@@ -123,13 +123,14 @@ typedef Tile<I8, 128, 128, 2, 2, 4, 2> I8_128x128;
 typedef Tile<I8, 64, 64, 2, 2, 4, 2> I8_64x64;
 
 // name, open to automatic selection (> 0), % of the solo-mode rate reached on large problems,
-// ns per K step of a workgroup that is alone on its CU
+// ns per K step of a workgroup that is alone on its CU, ns of fixed prologue cost (default 0)
 static const KernelInfo k_f32[] = {
     info<F32_128x128>("f32_128x128_w64x64", 0, 80, 2200),
     info<F32_256x128>("f32_256x128_w64x64", 0, 82, 3600),
     info<F32_64x64>("f32_64x64_w32x32", 1, 74, 780),
-    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 70, 900),
-    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 1, 90, 1400),
+    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 75, 800, 1200),
+    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 2, 4>>("f32_64x64_w32x32_dma", 1, 85, 650, 1200),
+    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 1, 93, 1300, 1200),
     info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 86, 2000),
 };
 static const KernelInfo k_f16[] = {
