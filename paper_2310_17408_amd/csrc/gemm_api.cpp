@@ -32,46 +32,72 @@ struct Choice { int id; int split; int ktiles_per_split; };
 // Cases", "Squared Matrices") and of the blocking-parameter model it cites for
 // the packed buffers.  For every candidate (tile configuration, K split) the
 // predicted time is
-//     launch + max(rounds * steps * step_time, staged_bytes / staging_bandwidth) + reduce(split)
-// where rounds  = ceil(tiles*split / (CUs * workgroups per CU)),
-//       steps   = ceil(K steps / split),
-//       step_time = max(co-resident workgroups * MFMA time of one K step, latency floor of a step),
-//       reduce  = second launch + split partial tiles written and read back.
-// The constants are measured on MI355X: sustained MFMA rate per data type (solo mode on random
-// data), 14 TB/s from L2 into LDS for GEMM-like tile streams, the time of a K step when a
-// workgroup is alone on its CU (per configuration), 2 TB/s for the partial-tile round trip, 4 us per launch.
+//     launch + fixed cost + main + reduce(split)
+// Kernels that stage tiles in LDS:
+//     main    = max(rounds * steps * step_time, staged_bytes / staging_bandwidth)
+//     rounds  = tiles*split / (CUs * workgroups per CU), at least 1
+//     steps   = ceil(K steps / split)
+//     step_time = max(co-resident workgroups * MFMA time of one K step, latency of a step);
+//                 the latency doubles when fewer than 0.6 workgroups per CU are in flight
+// Register-direct kernels (every wave streams its own operands):
+//     main    = max(rounds * steps per wave * step time of a lone wave,
+//                   MFMA time of all wave tiles, bytes all waves load / cache fill rate)
+//     rounds  = waves / (SIMDs * waves per SIMD), at least 1
+// reduce = second launch + split partial tiles written and read back.
+// The constants are measured on MI355X with HIP-graph replays: sustained MFMA rate per data type
+// (solo mode on random data), 14 TB/s from L2 into LDS for GEMM-like tile streams, 2 TB/s for the
+// partial-tile round trip, 2.5 us per launch, 3.3 us for the second launch.
 // ---------------------------------------------------------------------------
 constexpr double kSustainedTflops[3] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61};
 constexpr double kStagingBytesPerUs = 14.0e6;
 constexpr double kStepFloorUs = 0.75;
+constexpr double kLowOccupancy = 0.6, kLowOccupancyLatency = 2.0;
 constexpr double kReduceBytesPerUs = 2.0e6;
-constexpr double kLaunchUs = 4.0;
+constexpr double kLaunchUs = 2.5, kReduceLaunchUs = 3.3;
 constexpr int kMaxAutoSplit = 16;
+constexpr int NUM_SIMD = 4 * NUM_CU;
 
 double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split)
 {
     static const int es[3] = {4, 2, 1};
     const double tiles = (double)(ceil_div(M, ki->BM) * ceil_div(N, ki->BN));
     const double ktiles = (double)ceil_div(K, ki->BK);
-    const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
-    const double wgs = tiles * split;
-    // workgroups are dealt to free slots as they come, so beyond one round the count is fractional
-    double rounds = wgs / ((double)NUM_CU * occ);
-    rounds = rounds <= 1.0 ? 1.0 : (double)ceil_div((int64_t)(rounds * 4.0), 1) / 4.0;
-    double resident = wgs / NUM_CU;                                  // workgroups sharing a CU, on average
-    if (resident < 1.0) resident = 1.0;
-    if (resident > occ) resident = occ;
     const double steps = (double)ceil_div((int64_t)ktiles, split);
     const double eff = (ki->eff_pct > 0 ? ki->eff_pct : 100) / 100.0;
-    const double mfma_step = 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
-    double step = resident * mfma_step;
-    const double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
-    if (step < floor_us) step = floor_us;
-    double main_us = rounds * steps * step;
-    const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
-    if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
+    double main_us;
+    if (ki->waves_k > 0) {
+        const double wave_tiles = tiles * (ki->BM / ki->wave_m) * (ki->BN / ki->wave_n);
+        const double waves = wave_tiles * ki->waves_k * split;
+        double rounds = waves / ((double)NUM_SIMD * ki->waves_per_simd);
+        if (rounds < 1.0) rounds = 1.0;
+        const double steps_per_wave = (double)ceil_div((int64_t)steps, ki->waves_k);
+        const double chain = rounds * steps_per_wave * ki->step_floor_ns * 1e-3;
+        const double mfma = 2.0 * wave_tiles * ki->wave_m * ki->wave_n * ktiles * ki->BK /
+                            (kSustainedTflops[dtype] * 1e6 * eff);
+        const double fill = wave_tiles * ktiles * (double)(ki->wave_m + ki->wave_n) * ki->BK * es[dtype] /
+                            ki->fill_bytes_per_us;
+        main_us = chain > mfma ? chain : mfma;
+        if (fill > main_us) main_us = fill;
+    } else {
+        const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
+        const double wgs = tiles * split;
+        // workgroups are dealt to free slots as they come, so beyond one round the count is fractional
+        double rounds = wgs / ((double)NUM_CU * occ);
+        rounds = rounds <= 1.0 ? 1.0 : (double)ceil_div((int64_t)(rounds * 4.0), 1) / 4.0;
+        double resident = wgs / NUM_CU;                                  // workgroups sharing a CU, on average
+        if (resident < 1.0) resident = 1.0;
+        if (resident > occ) resident = occ;
+        const double mfma_step = 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
+        double step = resident * mfma_step;
+        double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
+        if (wgs < kLowOccupancy * NUM_CU) floor_us *= kLowOccupancyLatency;
+        if (step < floor_us) step = floor_us;
+        main_us = rounds * steps * step;
+        const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
+        if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
+    }
     double reduce_us = 0.0;
-    if (split > 1) reduce_us = kLaunchUs + (double)split * (double)M * (double)N * 8.0 / kReduceBytesPerUs;
+    if (split > 1) reduce_us = kReduceLaunchUs + (double)split * (double)M * (double)N * 8.0 / kReduceBytesPerUs;
     return kLaunchUs + ki->setup_ns * 1e-3 + main_us + reduce_us;
 }
 
@@ -88,15 +114,21 @@ int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K,
     return best;
 }
 
+// Leading dimensions (canonical problem) a configuration can address.
+bool can_address(const KernelInfo *ki, int64_t lda, int64_t ldb)
+{
+    return (ki->max_lda == 0 || lda <= ki->max_lda) && (ki->max_ldb == 0 || ldb <= ki->max_ldb);
+}
+
 // Best (configuration, split) over the configurations open to automatic selection (prio > 0).
-int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t max_split_bytes_per_mn)
+int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t max_split_bytes_per_mn)
 {
     const int n = kernel_count(dtype);
     int best = -1;
     double best_us = 0.0;
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        if (ki->prio <= 0) continue;
+        if (ki->prio <= 0 || !can_address(ki, lda, ldb)) continue;
         const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn);
         const double t = predict_us(dtype, ki, M, N, K, s);
         if (best < 0 || t < best_us) { best = id; best_us = t; }
@@ -104,7 +136,7 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t max_split_by
     return best < 0 ? 0 : best;
 }
 
-Choice choose(int dtype, int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool have_ws)
+Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws)
 {
     Choice c;
     const Forced f = g_forced[dtype];
@@ -113,7 +145,8 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, size_t ws_bytes, bool 
     int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
     if (fit > MAX_SPLIT) fit = MAX_SPLIT;
     if (fit < 1) fit = 1;
-    c.id = (f.id >= 0 && f.id < kernel_count(dtype)) ? f.id : auto_kernel(dtype, M, N, K, fit);
+    const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb);
+    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
     int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit);
@@ -172,7 +205,7 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
         return e == hipSuccess ? 0 : (int)e;
     }
 
-    const Choice ch = choose(dtype, Mc, Nc, K, ws_bytes, ws != nullptr);
+    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr);
     const KernelInfo *ki = kernel_info(dtype, ch.id);
 
     Params p;
@@ -303,7 +336,8 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
     if (N <= 0 || N > INT_MAX) return -4;
     if (K <= 0 || K > INT_MAX) return -5;
     const bool col = (layout == MI_GEMM_COL_MAJOR);
-    const Choice ch = choose(dtype, col ? M : N, col ? N : M, K, workspace_bytes, workspace_bytes > 0);
+    // tight leading dimensions: canonical A has M' contiguous, canonical B has K contiguous
+    const Choice ch = choose(dtype, col ? M : N, col ? N : M, K, col ? M : N, K, workspace_bytes, workspace_bytes > 0);
     if (kernel_id) *kernel_id = ch.id;
     if (split) *split = ch.split;
     return 0;

@@ -181,13 +181,15 @@ __device__ __forceinline__ void tile_coords(const Params &p, int bid, int &tm, i
 // when K is split.  In every 32 x 32 block a lane holds one row m and the 16
 // columns n = 8*(v/4) + 4*(lane/32) + v%4, so the 32 lanes of a half-wave write
 // 128 contiguous bytes of a column of C.
+// A tile that was moved back to end at the edge of C (m0 < m_own or n0 < n_own) stores only the
+// rows from m_own and the columns from n_own on; the rest belongs to its neighbours.
 template <class DT, int TM, int TN>
 __device__ __forceinline__ void store_tile(typename DT::accv (&acc)[TM][TN], const Params &p, int m0, int n0, int BM,
-                                           int BN, int wm0, int wn0, int lane, int z)
+                                           int BN, int wm0, int wn0, int lane, int z, int m_own, int n_own)
 {
     typedef typename DT::acc_t acc_t;
     const int frow = lane & 31, fgrp = lane >> 5;
-    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N) && m0 == m_own && n0 == n_own;
     const acc_t alpha = __builtin_bit_cast(acc_t, p.alpha_bits);
     const acc_t beta = __builtin_bit_cast(acc_t, p.beta_bits);
     const bool use_beta = p.use_beta != 0;
@@ -199,7 +201,7 @@ __device__ __forceinline__ void store_tile(typename DT::accv (&acc)[TM][TN], con
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int n = n0 + wn0 + 32 * j + 8 * (v >> 2) + 4 * fgrp + (v & 3);
-                if (interior || (m < p.M && n < p.N)) {
+                if (interior || (m >= m_own && m < p.M && n >= n_own && n < p.N)) {
                     const acc_t a = acc[i][j][v];
                     if (p.split > 1) {
                         acc_t *ws = (acc_t *)p.ws;
@@ -434,7 +436,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
         }
     }
 
-    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z);
+    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z, m0, n0);
 }
 
 // ---------------------------------------------------------------- helpers
@@ -452,15 +454,33 @@ __global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ w
         const int m = (int)(idx % M);
         const int64_t n = idx / M;
         acc_t *c = C + n * ldc + m;
-        if constexpr (sizeof(acc_t) == 4 && __is_same(acc_t, int)) {
+        // the partial tiles are added in the order of their K slices; 8 loads are in flight at a time
+        const acc_t *src = ws + idx;
+        if constexpr (__is_same(acc_t, int)) {
             uint32_t s = 0;
-            for (int zz = 0; zz < split; ++zz) s += (uint32_t)ws[(int64_t)zz * total + idx];
+            int zz = 0;
+            for (; zz + 8 <= split; zz += 8) {
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = (uint32_t)src[(int64_t)(zz + u) * total];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s += v[u];
+            }
+            for (; zz < split; ++zz) s += (uint32_t)src[(int64_t)zz * total];
             uint32_t r = (uint32_t)alpha * s;
             if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
             *c = (int)r;
         } else {
             acc_t s = 0;
-            for (int zz = 0; zz < split; ++zz) s += ws[(int64_t)zz * total + idx];
+            int zz = 0;
+            for (; zz + 8 <= split; zz += 8) {
+                acc_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(zz + u) * total];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s += v[u];
+            }
+            for (; zz < split; ++zz) s += src[(int64_t)zz * total];
             acc_t r = alpha * s;
             if (use_beta) r += beta * (*c);
             *c = r;

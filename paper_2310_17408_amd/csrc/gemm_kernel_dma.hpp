@@ -200,7 +200,12 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
 
     int tm, tn;
     tile_coords(p, blockIdx.x, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    // A tile that sticks out of C is moved back so that it ends at the edge, when the matrix is at
+    // least one tile wide and the moved tile keeps the 16-byte alignment of its rows: it then takes
+    // the direct transfers of an interior tile and stores only the part no other tile owns.
+    const int m_own = tm * BM, n_own = tn * BN;
+    const int m0 = (m_own + BM > p.M && p.M >= BM && (p.M * ES) % 16 == 0) ? p.M - BM : m_own;
+    const int n0 = (n_own + BN > p.N && p.N >= BN) ? p.N - BN : n_own;
 
     const int z = blockIdx.y;
     const int kt_begin = z * p.ktiles_per_split;
@@ -372,7 +377,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
         }
     }
 
-    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z);
+    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z, m_own, n_own);
 }
 
 }  // namespace mig

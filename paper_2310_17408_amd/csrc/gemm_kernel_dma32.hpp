@@ -157,7 +157,12 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
 
     int tm, tn;
     tile_coords(p, blockIdx.x, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    // A tile that sticks out of C is moved back so that it ends at the edge (when the matrix is at
+    // least one tile wide): it then reads only rows that exist, through the same transfers as an
+    // interior tile, and stores only the part no other tile owns (from m_own, n_own on).
+    const int m_own = tm * BM, n_own = tn * BN;
+    const int m0 = (m_own + BM > p.M && p.M >= BM) ? p.M - BM : m_own;
+    const int n0 = (n_own + BN > p.N && p.N >= BN) ? p.N - BN : n_own;
 
     const int z = blockIdx.y;
     const int kt_begin = z * p.ktiles_per_split;
@@ -170,7 +175,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
     // tile rows all inside the matrix, and a lane's 32-bit byte offset inside a block cannot overflow
     const bool in_a = (m0 + BM <= p.M) && (p.lda < (1 << 26));
     const bool in_b = (n0 + BN <= p.N) && (p.ldb < (1 << 26));
-    const bool a16 = p.vecA != 0, b16 = p.vecB != 0;                // rows are 16-byte aligned
+    // rows are 16-byte aligned (a moved tile of A may start at any m)
+    const bool a16 = p.vecA != 0 && (m0 % 4 == 0), b16 = p.vecB != 0;
 
     // ---- staging.  A stage is cut into 1 KiB blocks, block `blk` of an operand belongs to wave
     // blk % NW.  16-byte path: one transfer per block.  4-byte path: four 256-byte transfers.
@@ -394,7 +400,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
 
     // ---- epilogue: a lane holds, per block column n, the TM consecutive rows m it owns
     {
-        const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+        const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N) && m0 == m_own && n0 == n_own;
         const float alpha = __builtin_bit_cast(float, p.alpha_bits);
         const float beta = __builtin_bit_cast(float, p.beta_bits);
         const bool use_beta = p.use_beta != 0;
@@ -410,7 +416,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
                     float *ws = (float *)p.ws + ((int64_t)z * p.N + n) * p.M + mrow;
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
-                        if (interior || (mrow + i < p.M && n < p.N)) ws[i] = acc[i][j][v];
+                        if (interior || (mrow + i >= m_own && mrow + i < p.M && n >= n_own && n < p.N)) ws[i] = acc[i][j][v];
                 } else {
                     float *c = (float *)p.C + (int64_t)n * p.ldc + mrow;
                     if (vec_c) {
@@ -429,7 +435,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
                     } else {
 #pragma unroll
                         for (int i = 0; i < TM; ++i) {
-                            if (interior || (mrow + i < p.M && n < p.N)) {
+                            if (interior || (mrow + i >= m_own && mrow + i < p.M && n >= n_own && n < p.N)) {
                                 float r = alpha * acc[i][j][v];
                                 if (use_beta) r += beta * c[i];
                                 c[i] = r;

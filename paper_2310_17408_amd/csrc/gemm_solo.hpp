@@ -9,6 +9,7 @@
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
+#include "gemm_kernel_reg32.hpp"
 
 namespace mig {
 
@@ -102,6 +103,36 @@ __global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_direct(int ksteps,
             Micro::mma(fa[s & 1], fb[s & 1], acc);
             __builtin_amdgcn_sched_barrier(0);
         }
+    }
+    solo_finish(acc);
+}
+
+// register-direct kernels (gemm_kernel_reg32.hpp): the operands of one K step stay in registers
+template <class T>
+__global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_reg(int ksteps, int fill)
+{
+    typedef RegMicro<T> Micro;
+    typename Micro::aset fa;
+    typename Micro::bset fb;
+#pragma unroll
+    for (int t = 0; t < T::KG; ++t) {
+#pragma unroll
+        for (int i = 0; i < T::TM; ++i)
+            fa.v[t][i] = __builtin_bit_cast(float, solo_word<4>((uint32_t)(threadIdx.x * 64 + t * 4 + i) * 4u, fill));
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+            fb.v[j][t] = __builtin_bit_cast(float, solo_word<4>((uint32_t)(threadIdx.x * 64 + 32 + t * 4 + j) * 4u, fill));
+    }
+    typename Micro::accv acc[T::TM][T::TN];
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < T::ACC; ++v) acc[i][j][v] = 0;
+    for (int it = 0; it < ksteps; ++it) {
+        Micro::mma(fa, fb, acc);
+        __builtin_amdgcn_sched_barrier(0);
     }
     solo_finish(acc);
 }

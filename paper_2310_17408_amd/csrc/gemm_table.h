@@ -42,6 +42,13 @@ struct KernelInfo {
     // operands resident in LDS (fill 0: zeros, 1: pseudo-random finite values).
     hipError_t (*solo)(int workgroups, int ksteps, int fill, hipStream_t);
     int min_blocks_per_cu;   // workgroups per CU the kernel is built to co-reside with
+    int64_t max_lda, max_ldb;  // largest canonical leading dimensions the kernel's 32-bit lane offsets allow (0: any)
+    // Register-direct kernels (0 for the others): the tile of C one wave owns, the number of waves
+    // that share it along K, waves per SIMD that fit, and the rate at which the chip fills the
+    // vector caches for wave tiles of that size (bytes per microsecond).  For these kernels
+    // step_floor_ns is the time of one K step of a wave that has its SIMD to itself.
+    int wave_m, wave_n, waves_k, waves_per_simd;
+    double fill_bytes_per_us;
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8

@@ -4,6 +4,7 @@
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
+#include "gemm_kernel_reg32.hpp"
 #include "gemm_solo.hpp"
 #include "gemm_table.h"
 
@@ -105,6 +106,29 @@ static constexpr KernelInfo info_dma32(const char *name, int prio, int eff_pct, 
 }
 
 template <class T>
+static hipError_t launch_tile_reg32(const Params &p, hipStream_t stream)
+{
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL(gemm_kernel_reg32<T>, grid, dim3(T::NT), 0, stream, p);   // its LDS is static
+    return hipGetLastError();
+}
+template <class T>
+static hipError_t solo_reg32(int wg, int ks, int fill, hipStream_t st)
+{
+    hipLaunchKernelGGL(solo_kernel_reg<T>, dim3((unsigned)wg), dim3(T::NT), 0, st, ks, fill);
+    return hipGetLastError();
+}
+
+template <class T>
+static constexpr KernelInfo info_reg32(const char *name, int prio, int eff_pct, int step_ns, int setup_ns,
+                                       int waves_per_simd)
+{
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg32<T>, prio, eff_pct, step_ns, setup_ns,
+                      &solo_reg32<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
+                      T::WM * T::WN <= 256 ? 12.5e6 : 9.5e6};
+}
+
+template <class T>
 static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, setup_ns, &solo_staged<T>, T::MINB};
@@ -112,6 +136,7 @@ static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int fl
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU
 // Direct-to-LDS:    dtype BM   BN  waves  fragment steps per stage, stages, min workgroups per CU
+// Register-direct:  MFMA block, blocks per wave tile (m, n), waves (m, n, k), K steps in flight, min workgroups per CU
 typedef Tile<F32, 128, 128, 2, 2, 4, 2> F32_128x128;
 typedef Tile<F32, 256, 128, 4, 2, 4, 1> F32_256x128;
 typedef Tile<F32, 64, 64, 2, 2, 2, 2> F32_64x64;
@@ -123,29 +148,37 @@ typedef Tile<I8, 128, 128, 2, 2, 4, 2> I8_128x128;
 typedef Tile<I8, 64, 64, 2, 2, 4, 2> I8_64x64;
 
 // name, open to automatic selection (> 0), % of the solo-mode rate reached on large problems,
-// ns per K step of a workgroup that is alone on its CU, ns of fixed prologue cost (default 0)
+// ns per K step of a workgroup that is alone on its CU, ns of fixed cost per launch beyond the launch itself.
+// Register-direct kernels: % of the MFMA rate reached when many waves share a SIMD, ns per K step of a
+// wave alone on its SIMD, ns of fixed cost, waves per SIMD.  All measured (graph replay, MI355X).
 static const KernelInfo k_f32[] = {
-    info<F32_128x128>("f32_128x128_w64x64", 0, 80, 2200),
-    info<F32_256x128>("f32_256x128_w64x64", 0, 82, 3600),
-    info<F32_64x64>("f32_64x64_w32x32", 1, 74, 780),
-    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 75, 800, 1200),
-    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 2, 4>>("f32_64x64_w32x32_dma", 1, 85, 650, 1200),
-    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 1, 93, 1300, 1200),
-    info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 86, 2000),
+    info<F32_128x128>("f32_128x128_w64x64", 0, 80, 2200, 1500),
+    info<F32_256x128>("f32_256x128_w64x64", 0, 82, 3600, 1500),
+    info<F32_64x64>("f32_64x64_w32x32", 1, 74, 780, 1500),
+    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 5, 2>>("f32_64x64_w32x32_dma_s5", 0, 75, 800, 2700),
+    info_dma32<Dma32Tile<64, 64, 2, 2, 4, 2, 4>>("f32_64x64_w32x32_dma", 1, 85, 600, 1500),
+    info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 1, 93, 1300, 2700),
+    info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 86, 2000, 1500),
+    info_reg32<RegTile<16, 1, 1, 2, 2, 1, 12, 4>>("f32_32x32_w16x16_reg", 1, 45, 133, 200, 4),
+    info_reg32<RegTile<16, 2, 2, 2, 2, 1, 8, 2>>("f32_64x64_w32x32_reg16", 1, 60, 387, 0, 2),
+    info_reg32<RegTile<16, 1, 1, 1, 1, 4, 12, 4>>("f32_16x16_k4_reg", 1, 45, 150, 400, 4),
+    info_reg32<RegTile<16, 1, 1, 1, 1, 8, 12, 2>>("f32_16x16_k8_reg", 1, 45, 150, 600, 4),
+    info_reg32<RegTile<32, 1, 1, 1, 1, 4, 6, 2>>("f32_32x32_k4_reg", 1, 60, 335, 700, 3),
+    info_reg32<RegTile<16, 2, 2, 1, 1, 4, 8, 2>>("f32_32x32_k4_reg16", 1, 60, 400, 500, 2),
 };
 static const KernelInfo k_f16[] = {
-    info<F16_256x256>("f16_256x256_w128x128", 0, 50, 2500),
-    info<F16_128x128>("f16_128x128_w64x64", 0, 47, 1700),
-    info<F16_64x64>("f16_64x64_w32x32", 1, 40, 600),
-    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 1, 72, 880),
-    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 1, 82, 1800),
+    info<F16_256x256>("f16_256x256_w128x128", 0, 50, 2500, 1500),
+    info<F16_128x128>("f16_128x128_w64x64", 0, 47, 1700, 1500),
+    info<F16_64x64>("f16_64x64_w32x32", 1, 40, 600, 1500),
+    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 1, 72, 880, 1500),
+    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 1, 82, 1800, 1500),
 };
 static const KernelInfo k_i8[] = {
-    info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500),
-    info<I8_128x128>("i8_128x128_w64x64", 0, 47, 800),
-    info<I8_64x64>("i8_64x64_w32x32", 1, 30, 600),
-    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 1, 62, 880),
-    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 1, 75, 1800),
+    info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500, 1500),
+    info<I8_128x128>("i8_128x128_w64x64", 0, 47, 800, 1500),
+    info<I8_64x64>("i8_64x64_w32x32", 1, 30, 600, 1500),
+    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 1, 62, 880, 1500),
+    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 1, 75, 1800, 1500),
 };
 
 int kernel_count(int dtype)

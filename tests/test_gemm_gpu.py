@@ -58,6 +58,17 @@ def test_every_kernel_ragged(dtype, layout):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_every_kernel_edge_tiles_with_aligned_rows(dtype, layout):
+    """M and N that are multiples of 16 elements but of no tile size: the edge tiles of the direct
+    kernels overlap their neighbours and must store only their own part (beta != 0, also with K split)."""
+    for kid in _kernels(dtype):
+        a, b = (1.5, 0.5) if dtype != "i8" else (3, -2)
+        check_case(dtype, layout, 304, 272, 256, a, b, seed=2500 + kid, kernel_id=kid)
+        check_case(dtype, layout, 336, 80, 1280, a, b, seed=2600 + kid, kernel_id=kid, split=3)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_tile_minus_plus_one(dtype):
     for kid in _kernels(dtype):
         for d in (-1, 1):
@@ -72,9 +83,10 @@ def test_split_k(dtype, layout):
         for split in (2, 5):
             k, s = check_case(dtype, layout, 200, 136, 2100, 1, 1, seed=3000 + kid, kernel_id=kid, split=split)
             assert s > 1
-    # automatic selection on a skinny problem picks a split, and no workspace falls back to none
+    # automatic selection on a skinny problem splits K, over workgroups or over the waves that share
+    # a tile in a register-direct kernel; no workspace falls back to no split over workgroups
     k, s = check_case(dtype, layout, 49, 512, 4608, 1, 0, seed=3100)
-    assert s > 1
+    assert s > 1 or "_k" in mg.gemm_kernel_name(DT[dtype], k)
     k, s = check_case(dtype, layout, 49, 512, 4608, 1, 0, seed=3100, workspace_bytes=0)
     assert s == 1
 
@@ -254,7 +266,7 @@ def test_solo_mode_runs_every_kernel(dtype):
     """The micro-kernel benchmark launches and completes for every tile configuration."""
     for kid in _kernels(dtype):
         bm, bn, bk, wpc = mg.gemm_kernel_tile(DT[dtype], kid)
-        assert bm % 32 == 0 and bn % 32 == 0 and bk > 0 and wpc >= 1
+        assert bm % 16 == 0 and bn % 16 == 0 and bk > 0 and wpc >= 1
         for fill in (0, 1):
             assert mg.gemm_solo(DT[dtype], kid, 64, 50, fill) == 0
     torch.cuda.synchronize()
