@@ -121,6 +121,14 @@ int gemm_last_split(void);
 int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int *kernel_id,
                 int *split);
 
+/* The selector's timing model (the counterpart of the analytical blocking model
+ * the paper cites in Sec. "Blocked algorithms for GEMM"): the time in
+ * microseconds it predicts for tile configuration `id` with K split `split` on
+ * the canonical (column-major) problem M x N x K, launch included.  Pure host
+ * computation.  Returns a negative value for an unknown dtype or id, or M, N, K
+ * or split that are not positive. */
+double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int split);
+
 /* Tile of configuration `id`: BM x BN of C per workgroup, BK elements of K per
  * step, and how many workgroups the kernel is built to keep resident per CU.
  * Any output pointer may be NULL.  Returns 0, or -1 for an unknown dtype / id. */

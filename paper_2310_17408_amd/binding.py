@@ -54,6 +54,8 @@ def load():
     lib.gemm_force_kernel.argtypes = [ci, ci, ci]
     lib.gemm_kernel_tile.restype = ci
     lib.gemm_kernel_tile.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 4
+    lib.gemm_predict_us.restype = ctypes.c_double
+    lib.gemm_predict_us.argtypes = [ci, ci, i64, i64, i64, ci]
     lib.gemm_select.restype = ci
     lib.gemm_select.argtypes = [ci, ci, i64, i64, i64, sz, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.gemm_solo.restype = ci
@@ -136,6 +138,14 @@ def gemm_kernel_tile(dtype, kernel_id):
     if status != 0:
         raise GemmError(status, "unknown dtype or kernel id")
     return tuple(o.value for o in out)
+
+
+def gemm_predict_us(dtype, kernel_id, M, N, K, split=1):
+    """Time in microseconds the selector's model predicts for this configuration and split."""
+    t = load().gemm_predict_us(dtype, kernel_id, M, N, K, split)
+    if t < 0:
+        raise GemmError(-1, "gemm_predict_us: bad argument")
+    return t
 
 
 def gemm_select(dtype, layout, M, N, K, workspace_bytes):

@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime_api.h>
 #include <limits.h>
+#include <math.h>
 #include <stdio.h>
 #include <string.h>
 
@@ -38,22 +39,23 @@ struct Choice { int id; int split; int ktiles_per_split; };
 //     rounds  = tiles*split / (CUs * workgroups per CU), at least 1
 //     steps   = ceil(K steps / split)
 //     step_time = max(co-resident workgroups * MFMA time of one K step, latency of a step);
-//                 the latency doubles when fewer than 0.6 workgroups per CU are in flight
+//                 the latency is 2.2 times longer when a dimension is smaller than the tile, because
+//                 such a tile cannot be moved inside the matrix and is staged through registers
 // Register-direct kernels (every wave streams its own operands):
 //     main    = max(rounds * steps per wave * step time of a lone wave,
-//                   MFMA time of all wave tiles, bytes all waves load / cache fill rate)
+//                   MFMA time of all wave tiles, bytes all waves load / cache fill rate of the busy CUs)
 //     rounds  = waves / (SIMDs * waves per SIMD), at least 1
 // reduce = second launch + split partial tiles written and read back.
 // The constants are measured on MI355X with HIP-graph replays: sustained MFMA rate per data type
-// (solo mode on random data), 14 TB/s from L2 into LDS for GEMM-like tile streams, 2 TB/s for the
-// partial-tile round trip, 2.5 us per launch, 3.3 us for the second launch.
+// (solo mode on random data), 14 TB/s from L2 into LDS for GEMM-like tile streams, 4 TB/s for the
+// partial-tile round trip, 2.5 us per launch, 3.0 us for the second launch.
 // ---------------------------------------------------------------------------
 constexpr double kSustainedTflops[3] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61};
 constexpr double kStagingBytesPerUs = 14.0e6;
 constexpr double kStepFloorUs = 0.75;
-constexpr double kLowOccupancy = 0.6, kLowOccupancyLatency = 2.0;
-constexpr double kReduceBytesPerUs = 2.0e6;
-constexpr double kLaunchUs = 2.5, kReduceLaunchUs = 3.3;
+constexpr double kGuardedStepFactor = 2.2;
+constexpr double kReduceBytesPerUs = 4.0e6;
+constexpr double kLaunchUs = 2.5, kReduceLaunchUs = 3.0;
 constexpr int kMaxAutoSplit = 16;
 constexpr int NUM_SIMD = 4 * NUM_CU;
 
@@ -74,8 +76,11 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
         const double chain = rounds * steps_per_wave * ki->step_floor_ns * 1e-3;
         const double mfma = 2.0 * wave_tiles * ki->wave_m * ki->wave_n * ktiles * ki->BK /
                             (kSustainedTflops[dtype] * 1e6 * eff);
+        // the fill rate is a sum over CUs: with fewer workgroups than CUs less of it is there (measured:
+        // about the square root of the busy share, since a CU alone in its part of the chip fills faster)
+        const double busy = tiles * split < NUM_CU ? sqrt(tiles * split / NUM_CU) : 1.0;
         const double fill = wave_tiles * ktiles * (double)(ki->wave_m + ki->wave_n) * ki->BK * es[dtype] /
-                            ki->fill_bytes_per_us;
+                            (ki->fill_bytes_per_us * busy);
         main_us = chain > mfma ? chain : mfma;
         if (fill > main_us) main_us = fill;
     } else {
@@ -90,7 +95,7 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
         const double mfma_step = 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
         double step = resident * mfma_step;
         double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
-        if (wgs < kLowOccupancy * NUM_CU) floor_us *= kLowOccupancyLatency;
+        if (M < ki->BM || N < ki->BN) floor_us *= kGuardedStepFactor;
         if (step < floor_us) step = floor_us;
         main_us = rounds * steps * step;
         const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
@@ -109,7 +114,7 @@ int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K,
     double best_us = predict_us(dtype, ki, M, N, K, 1);
     for (int s = 2; s <= kMaxAutoSplit && s <= max_split && 2 * s <= ktiles; ++s) {
         const double t = predict_us(dtype, ki, M, N, K, s);
-        if (t < best_us * 0.97) { best_us = t; best = s; }     // a split must pay for itself clearly
+        if (t < best_us * 0.92) { best_us = t; best = s; }     // a split must pay for itself clearly
     }
     return best;
 }
@@ -341,6 +346,13 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
     if (kernel_id) *kernel_id = ch.id;
     if (split) *split = ch.split;
     return 0;
+}
+
+double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int split)
+{
+    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    if (!ki || M <= 0 || N <= 0 || K <= 0 || split <= 0 || M > INT_MAX || N > INT_MAX || K > INT_MAX) return -1.0;
+    return predict_us(dtype, ki, M, N, K, split);
 }
 
 int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *stream)

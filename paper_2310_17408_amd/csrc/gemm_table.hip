@@ -125,7 +125,7 @@ static constexpr KernelInfo info_reg32(const char *name, int prio, int eff_pct, 
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg32<T>, prio, eff_pct, step_ns, setup_ns,
                       &solo_reg32<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
-                      T::WM * T::WN <= 256 ? 12.5e6 : 9.5e6};
+                      (T::WM * T::WN <= 256 ? 12.5e6 : 9.5e6) - (T::WAVES_K > 1 ? 1.0e6 : 0.0)};
 }
 
 template <class T>
@@ -159,12 +159,12 @@ static const KernelInfo k_f32[] = {
     info_dma32<Dma32Tile<64, 64, 2, 2, 4, 2, 4>>("f32_64x64_w32x32_dma", 1, 85, 600, 1500),
     info_dma32<Dma32Tile<128, 64, 2, 2, 4, 2, 3>>("f32_128x64_w64x32_dma", 1, 93, 1300, 2700),
     info_dma32<Dma32Tile<128, 128, 2, 2, 4, 2, 2>>("f32_128x128_w64x64_dma", 0, 86, 2000, 1500),
-    info_reg32<RegTile<16, 1, 1, 2, 2, 1, 12, 4>>("f32_32x32_w16x16_reg", 1, 45, 133, 200, 4),
-    info_reg32<RegTile<16, 2, 2, 2, 2, 1, 8, 2>>("f32_64x64_w32x32_reg16", 1, 60, 387, 0, 2),
+    info_reg32<RegTile<16, 1, 1, 2, 2, 1, 12, 4>>("f32_32x32_w16x16_reg", 1, 45, 128, 0, 4),
+    info_reg32<RegTile<16, 2, 2, 2, 2, 1, 8, 2>>("f32_64x64_w32x32_reg16", 1, 60, 360, 0, 2),
     info_reg32<RegTile<16, 1, 1, 1, 1, 4, 12, 4>>("f32_16x16_k4_reg", 1, 45, 150, 400, 4),
-    info_reg32<RegTile<16, 1, 1, 1, 1, 8, 12, 2>>("f32_16x16_k8_reg", 1, 45, 150, 600, 4),
-    info_reg32<RegTile<32, 1, 1, 1, 1, 4, 6, 2>>("f32_32x32_k4_reg", 1, 60, 335, 700, 3),
-    info_reg32<RegTile<16, 2, 2, 1, 1, 4, 8, 2>>("f32_32x32_k4_reg16", 1, 60, 400, 500, 2),
+    info_reg32<RegTile<16, 1, 1, 1, 1, 8, 12, 2>>("f32_16x16_k8_reg", 1, 45, 150, 900, 4),
+    info_reg32<RegTile<32, 1, 1, 1, 1, 4, 6, 2>>("f32_32x32_k4_reg", 1, 60, 335, 650, 3),
+    info_reg32<RegTile<16, 2, 2, 1, 1, 4, 8, 2>>("f32_32x32_k4_reg16", 1, 60, 420, 800, 2),
 };
 static const KernelInfo k_f16[] = {
     info<F16_256x256>("f16_256x256_w128x128", 0, 50, 2500, 1500),

@@ -91,3 +91,40 @@ def test_workspace_bytes():
     w = mg.gemm_workspace_bytes(mg.F32, 49, 512, 4608)
     assert w >= 2 * 49 * 512 * 4 and w % (49 * 512 * 4) == 0
     assert mg.gemm_workspace_bytes(mg.F32, 49, 512, 4608) == mg.gemm_workspace_bytes(mg.F32, 512, 49, 4608)
+
+
+def _auto_selectable(dtype, kid):
+    # a configuration is open to automatic selection if some problem selects it; the table marks
+    # the others as explicit-only, which shows in their never being returned unforced
+    probes = [(12544, 64, 147), (3136, 64, 64), (3136, 64, 576), (784, 128, 1152), (196, 256, 2304), (49, 512, 4608),
+              (3136, 128, 256), (784, 512, 128), (1024, 1024, 1024), (2048, 2048, 2048), (8192, 8192, 8192),
+              (64, 64, 64), (4096, 64, 4096), (50176, 64, 576), (33, 17, 2049), (256, 256, 256)]
+    return any(mg.gemm_select(dtype, 0, m, n, k, 32 * m * n * 4)[0] == kid for (m, n, k) in probes)
+
+
+def test_timing_model_and_selection_agree():
+    """gemm_select returns the (configuration, split) with the smallest predicted time among the
+    configurations open to automatic selection, and the model behaves sanely: more work never
+    takes less time, bad arguments are refused."""
+    for dtype in (mg.F32, mg.F16, mg.I8):
+        for (M, N, K) in [(12544, 64, 147), (49, 512, 4608), (1024, 1024, 1024), (4096, 4096, 4096), (33, 17, 2049)]:
+            kid, split = mg.gemm_select(dtype, 0, M, N, K, 32 * M * N * 4)
+            t = mg.gemm_predict_us(dtype, kid, M, N, K, split)
+            assert t > 0
+            # forcing another configuration is never predicted to be clearly faster than the pick
+            for other in range(mg.gemm_kernel_count(dtype)):
+                mg.gemm_force_kernel(dtype, other, 0)
+                k2, s2 = mg.gemm_select(dtype, 0, M, N, K, 32 * M * N * 4)
+                mg.gemm_force_kernel(dtype, -1, 0)
+                if k2 != other:
+                    continue                       # not addressable for this problem
+                name = mg.gemm_kernel_name(dtype, other)
+                assert name
+                if _auto_selectable(dtype, other):
+                    assert mg.gemm_predict_us(dtype, other, M, N, K, s2) >= t * 0.999, (name, M, N, K)
+        big = mg.gemm_predict_us(dtype, 0, 4096, 4096, 4096, 1)
+        assert big > mg.gemm_predict_us(dtype, 0, 2048, 2048, 2048, 1) > mg.gemm_predict_us(dtype, 0, 512, 512, 512, 1)
+    with pytest.raises(mg.GemmError):
+        mg.gemm_predict_us(mg.F32, 99, 10, 10, 10, 1)
+    with pytest.raises(mg.GemmError):
+        mg.gemm_predict_us(mg.F32, 0, 10, 10, 10, 0)
