@@ -115,7 +115,8 @@ int gemm_last_split(void);
 
 /* What a call with these arguments would launch (pure host computation, nothing
  * runs): the tile configuration and the K split chosen by the selector - or the
- * forced ones - for a workspace of `workspace_bytes`.  Either output pointer may
+ * forced ones - for a workspace of `workspace_bytes`, operands with tight leading
+ * dimensions and 16-byte aligned base addresses.  Either output pointer may
  * be NULL.  Returns 0, or -1 unknown dtype, -2 unknown layout, -3/-4/-5 M/N/K
  * not positive or too large. */
 int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int *kernel_id,
@@ -124,8 +125,8 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
 /* The selector's timing model (the counterpart of the analytical blocking model
  * the paper cites in Sec. "Blocked algorithms for GEMM"): the time in
  * microseconds it predicts for tile configuration `id` with K split `split` on
- * the canonical (column-major) problem M x N x K, launch included.  Pure host
- * computation.  Returns a negative value for an unknown dtype or id, or M, N, K
+ * the canonical (column-major) problem M x N x K with 16-byte aligned operand
+ * rows, launch included.  Pure host computation.  Returns a negative value for an unknown dtype or id, or M, N, K
  * or split that are not positive. */
 double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int split);
 

@@ -59,7 +59,7 @@ constexpr double kLaunchUs = 2.5, kReduceLaunchUs = 3.0;
 constexpr int kMaxAutoSplit = 16;
 constexpr int NUM_SIMD = 4 * NUM_CU;
 
-double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split)
+double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split, bool aligned = true)
 {
     static const int es[3] = {4, 2, 1};
     const double tiles = (double)(ceil_div(M, ki->BM) * ceil_div(N, ki->BN));
@@ -97,6 +97,7 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
         double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
         if (M < ki->BM || N < ki->BN) floor_us *= kGuardedStepFactor;
         if (step < floor_us) step = floor_us;
+        if (!aligned && ki->unaligned_pct > 0) step *= 100.0 / ki->unaligned_pct;
         main_us = rounds * steps * step;
         const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
         if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
@@ -107,13 +108,13 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
 }
 
 // Best split for one configuration (used directly when the configuration is forced).
-int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split)
+int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split, bool aligned = true)
 {
     const int64_t ktiles = ceil_div(K, ki->BK);
     int best = 1;
-    double best_us = predict_us(dtype, ki, M, N, K, 1);
+    double best_us = predict_us(dtype, ki, M, N, K, 1, aligned);
     for (int s = 2; s <= kMaxAutoSplit && s <= max_split && 2 * s <= ktiles; ++s) {
-        const double t = predict_us(dtype, ki, M, N, K, s);
+        const double t = predict_us(dtype, ki, M, N, K, s, aligned);
         if (t < best_us * 0.92) { best_us = t; best = s; }     // a split must pay for itself clearly
     }
     return best;
@@ -126,7 +127,8 @@ bool can_address(const KernelInfo *ki, int64_t lda, int64_t ldb)
 }
 
 // Best (configuration, split) over the configurations open to automatic selection (prio > 0).
-int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t max_split_bytes_per_mn)
+int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t max_split_bytes_per_mn,
+                bool aligned)
 {
     const int n = kernel_count(dtype);
     int best = -1;
@@ -134,14 +136,15 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
         if (ki->prio <= 0 || !can_address(ki, lda, ldb)) continue;
-        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn);
-        const double t = predict_us(dtype, ki, M, N, K, s);
+        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned);
+        const double t = predict_us(dtype, ki, M, N, K, s, aligned);
         if (best < 0 || t < best_us) { best = id; best_us = t; }
     }
     return best < 0 ? 0 : best;
 }
 
-Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws)
+Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws,
+              bool aligned)
 {
     Choice c;
     const Forced f = g_forced[dtype];
@@ -151,10 +154,10 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     if (fit > MAX_SPLIT) fit = MAX_SPLIT;
     if (fit < 1) fit = 1;
     const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb);
-    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit);
+    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
-    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit);
+    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned);
     if (s > ktiles) s = ktiles;
     if (s > fit) s = fit;
     if (s < 1) s = 1;
@@ -210,7 +213,8 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
         return e == hipSuccess ? 0 : (int)e;
     }
 
-    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr);
+    const bool vec_a = aligned16(Ac, ldac, es), vec_b = aligned16(Bc, ldbc, es);
+    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr, vec_a && vec_b);
     const KernelInfo *ki = kernel_info(dtype, ch.id);
 
     Params p;
@@ -227,8 +231,8 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     p.alpha_bits = alpha_bits;
     p.beta_bits = beta_bits;
     p.use_beta = beta_zero ? 0 : 1;
-    p.vecA = aligned16(Ac, ldac, es) ? 1 : 0;
-    p.vecB = aligned16(Bc, ldbc, es) ? 1 : 0;
+    p.vecA = vec_a ? 1 : 0;
+    p.vecB = vec_b ? 1 : 0;
     p.group_m = 8;
     p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
 
@@ -280,9 +284,12 @@ size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
     int64_t smax = 1;
     for (int id = 0; id < kernel_count(dtype); ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT), s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT);
-        if (s1 > smax) smax = s1;
-        if (s2 > smax) smax = s2;
+        for (int aligned = 0; aligned < 2; ++aligned) {
+            const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT, aligned != 0);
+            const int64_t s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT, aligned != 0);
+            if (s1 > smax) smax = s1;
+            if (s2 > smax) smax = s2;
+        }
     }
     if (smax <= 1) return 0;
     return (size_t)smax * (size_t)M * (size_t)N * 4u;
@@ -341,8 +348,12 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
     if (N <= 0 || N > INT_MAX) return -4;
     if (K <= 0 || K > INT_MAX) return -5;
     const bool col = (layout == MI_GEMM_COL_MAJOR);
-    // tight leading dimensions: canonical A has M' contiguous, canonical B has K contiguous
-    const Choice ch = choose(dtype, col ? M : N, col ? N : M, K, col ? M : N, K, workspace_bytes, workspace_bytes > 0);
+    // tight leading dimensions and 16-byte aligned base addresses: canonical A has M' contiguous,
+    // canonical B has K contiguous
+    static const int es[3] = {4, 2, 1};
+    const int64_t Mc = col ? M : N, Nc = col ? N : M;
+    const bool aligned = (Mc * es[dtype]) % 16 == 0 && (K * es[dtype]) % 16 == 0;
+    const Choice ch = choose(dtype, Mc, Nc, K, Mc, K, workspace_bytes, workspace_bytes > 0, aligned);
     if (kernel_id) *kernel_id = ch.id;
     if (split) *split = ch.split;
     return 0;

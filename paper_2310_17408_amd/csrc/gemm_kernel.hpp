@@ -34,6 +34,12 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+// the same vectors at element alignment only: gfx950 serves global loads at any alignment
+// (the amdhsa target runs with unaligned access enabled), at the price of a second cache access
+// when a load straddles a line
+typedef int v4i_u __attribute__((ext_vector_type(4), aligned(1)));
+typedef int v2i_u __attribute__((ext_vector_type(2), aligned(1)));
+typedef int i32_u __attribute__((aligned(1)));
 
 // ---------------------------------------------------------------- data types
 struct F32 {
@@ -284,8 +290,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 
     const elt *__restrict__ A = (const elt *)p.A;
     const elt *__restrict__ B = (const elt *)p.B;
-    const bool tile_vec_a = p.vecA && (m0 + BM <= p.M);
-    const bool tile_vec_b = p.vecB && (n0 + BN <= p.N);
+    // interior tiles take whole-vector loads whatever the alignment of the operands
+    const bool tile_vec_a = (m0 + BM <= p.M);
+    const bool tile_vec_b = (n0 + BN <= p.N);
 
     accv acc[TM][TN];
 #pragma unroll
@@ -313,13 +320,13 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 #pragma unroll
                 for (int kk = 0; kk < KCH; ++kk) {
                     if constexpr (AW == 4) {
-                        v4i v = *(const v4i *)(src + (int64_t)kk * p.lda);
+                        v4i v = *(const v4i_u *)(src + (int64_t)kk * p.lda);
                         rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1]; rawA[it][kk][2] = v[2]; rawA[it][kk][3] = v[3];
                     } else if constexpr (AW == 2) {
-                        v2i v = *(const v2i *)(src + (int64_t)kk * p.lda);
+                        v2i v = *(const v2i_u *)(src + (int64_t)kk * p.lda);
                         rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1];
                     } else {
-                        rawA[it][kk][0] = *(const int *)(src + (int64_t)kk * p.lda);
+                        rawA[it][kk][0] = *(const i32_u *)(src + (int64_t)kk * p.lda);
                     }
                 }
             }
@@ -334,6 +341,19 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
                 for (int kk = 0; kk < KCH; ++kk) {
                     const int k = k0 + kch * KCH + kk;
                     const elt *src = A + (int64_t)k * p.lda + mb;
+                    if (k < p.K && mb + MB <= p.M) {
+                        // the whole vector exists: one load, whatever its alignment
+                        if constexpr (AW == 4) {
+                            const v4i v = *(const v4i_u *)src;
+                            rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1]; rawA[it][kk][2] = v[2]; rawA[it][kk][3] = v[3];
+                        } else if constexpr (AW == 2) {
+                            const v2i v = *(const v2i_u *)src;
+                            rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1];
+                        } else {
+                            rawA[it][kk][0] = *(const i32_u *)src;
+                        }
+                        continue;
+                    }
 #pragma unroll
                     for (int w = 0; w < AW; ++w) {
                         uint32_t word = 0;
@@ -360,7 +380,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
                 const int cid = tid + it * NT;
                 if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
                 const int row = cid >> 3, ch = cid & 7;
-                rawB[it] = *(const v4i *)(B + (int64_t)(n0 + row) * p.ldb + (k0 + ch * KCH));
+                rawB[it] = *(const v4i_u *)(B + (int64_t)(n0 + row) * p.ldb + (k0 + ch * KCH));
             }
         } else {
 #pragma unroll
@@ -371,6 +391,10 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
                 const int n = n0 + row;
                 const elt *src = B + (int64_t)n * p.ldb + (k0 + ch * KCH);
                 v4i v;
+                if (n < p.N && k0 + ch * KCH + KCH <= p.K) {
+                    rawB[it] = *(const v4i_u *)src;      // the whole chunk exists: one load at any alignment
+                    continue;
+                }
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     uint32_t word = 0;

@@ -94,6 +94,7 @@ template <class DT>
 __device__ __forceinline__ v4i guarded_chunk(const typename DT::elt *src, int valid)
 {
     constexpr int ES = DT::ES;
+    if (valid >= 16 / ES) return *(const v4i_u *)src;     // the whole chunk exists: one load at any alignment
     v4i v;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {

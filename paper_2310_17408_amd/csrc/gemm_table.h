@@ -20,7 +20,7 @@ struct Params {
     int split;             // gridDim.y
     uint32_t alpha_bits, beta_bits;
     int use_beta;          // beta != 0: the old C is read
-    int vecA, vecB;        // operand may be read with aligned vector loads
+    int vecA, vecB;        // operand rows are 16-byte aligned (direct global -> LDS transfers of 16 bytes)
     int group_m;           // tiles per column group in the tile order
     int xcd_remap;         // deal contiguous tile ranges to the 8 XCDs
 };
@@ -49,6 +49,10 @@ struct KernelInfo {
     // step_floor_ns is the time of one K step of a wave that has its SIMD to itself.
     int wave_m, wave_n, waves_k, waves_per_simd;
     double fill_bytes_per_us;
+    // Speed, in % of its normal one, when an operand's rows are not 16-byte aligned (0 = 100): the
+    // fp16/int8 kernels then load through misaligned vectors, which the memory system splits, and the
+    // direct ones stage every tile through registers.
+    int unaligned_pct;
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8

@@ -78,7 +78,8 @@ static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
 template <class T>
 static constexpr KernelInfo info_dma(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, eff_pct, floor_ns, setup_ns, &solo_dma<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, eff_pct, floor_ns, setup_ns,
+                      &solo_dma<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 30};
 }
 
 template <class T>
@@ -131,7 +132,8 @@ static constexpr KernelInfo info_reg32(const char *name, int prio, int eff_pct, 
 template <class T>
 static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, setup_ns, &solo_staged<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, setup_ns,
+                      &solo_staged<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, T::DT::ES == 4 ? 0 : 30};
 }
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU
