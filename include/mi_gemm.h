@@ -59,7 +59,7 @@ extern "C" {
 #endif
 
 enum { MI_GEMM_COL_MAJOR = 0, MI_GEMM_ROW_MAJOR = 1 };
-enum { MI_GEMM_F32 = 0, MI_GEMM_F16 = 1, MI_GEMM_I8 = 2 };
+enum { MI_GEMM_F32 = 0, MI_GEMM_F16 = 1, MI_GEMM_I8 = 2, MI_GEMM_BF16 = 3 };
 
 /* fp32 inputs and output, true fp32 MFMA arithmetic (no reduced-precision
  * splitting), fp32 accumulation.  Paper Sec. II-A; alpha/beta as in its
@@ -78,6 +78,16 @@ int gemm_f16(int layout, int64_t M, int64_t N, int64_t K,
              float beta, float *C, int64_t ldc,
              void *workspace, size_t workspace_bytes, void *stream);
 
+/* bfloat16 inputs (bit patterns: the upper 16 bits of an fp32), fp32 accumulation,
+ * fp32 C in and out.  Another precision of the paper's Sec. "Data types" (a
+ * micro-kernel is re-targeted by changing the type of its operands only); same
+ * arguments, layouts, alignment rules and error codes as gemm_f16. */
+int gemm_bf16(int layout, int64_t M, int64_t N, int64_t K,
+              float alpha, const uint16_t *A, int64_t lda,
+              const uint16_t *B, int64_t ldb,
+              float beta, float *C, int64_t ldc,
+              void *workspace, size_t workspace_bytes, void *stream);
+
 /* int8 inputs, int32 accumulation, int32 C in and out, int32 alpha and beta.
  * The result is exact (bit-for-bit) as long as the true value of every
  * intermediate fits in int32, which holds for K <= 131071 at alpha = 1,
@@ -89,7 +99,7 @@ int gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
             void *workspace, size_t workspace_bytes, void *stream);
 
 /* Upper bound of the workspace any split of the K loop may use for this
- * problem (dtype is one of MI_GEMM_F32/F16/I8); 0 if M, N or K is not positive. */
+ * problem (dtype is one of MI_GEMM_F32/F16/I8/BF16); 0 if M, N or K is not positive. */
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K);
 
 /* Text for a status returned by the entry points (static storage). */

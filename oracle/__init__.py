@@ -14,8 +14,10 @@ from .ref import (  # noqa: F401
     build,
     num_threads,
     half_to_double,
+    bfloat16_to_double,
     gemm_f32,
     gemm_f16,
+    gemm_bf16,
     gemm_i8,
     gemm_sample,
     wrap_int32,

@@ -38,7 +38,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         i64, f32, i32, vp, dbl = (ctypes.c_int64, ctypes.c_float, ctypes.c_int32,
                                   ctypes.c_void_p, ctypes.c_double)
-        for name, scal in (("ref_gemm_f32", f32), ("ref_gemm_f16", f32), ("ref_gemm_i8", i32)):
+        for name, scal in (("ref_gemm_f32", f32), ("ref_gemm_f16", f32), ("ref_gemm_bf16", f32), ("ref_gemm_i8", i32)):
             fn = getattr(lib, name)
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_int, i64, i64, i64, scal, vp, i64, vp, i64, scal, vp, i64, vp, i64]
@@ -47,6 +47,8 @@ def _load():
                                         dbl, vp, i64, i64, vp, vp, vp]
         lib.ref_half_to_double.restype = dbl
         lib.ref_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.ref_bfloat16_to_double.restype = dbl
+        lib.ref_bfloat16_to_double.argtypes = [ctypes.c_uint16]
         lib.ref_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -59,6 +61,10 @@ def num_threads():
 
 def half_to_double(bits):
     return float(_load().ref_half_to_double(int(bits) & 0xFFFF))
+
+
+def bfloat16_to_double(bits):
+    return float(_load().ref_bfloat16_to_double(int(bits) & 0xFFFF))
 
 
 def _ptr(a):
@@ -110,6 +116,12 @@ def gemm_f16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
                 layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
 
 
+def gemm_bf16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
+    """bfloat16 bit patterns (uint16) in, float32 C in; returns double (M, N)."""
+    return _run(_load().ref_gemm_bf16, np.uint16, np.float32, np.float64,
+                layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+
+
 def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
     """int8 inputs, int32 C in; returns the exact int64 result (M, N)."""
     return _run(_load().ref_gemm_i8, np.int8, np.int32, np.int64,
@@ -118,7 +130,7 @@ def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
 
 def gemm_sample(dtype, layout, K, alpha, A, lda, B, ldb, beta, C, ldc, rows, cols):
     """The definition evaluated at positions (rows[s], cols[s]) only; returns double[nsamp]."""
-    code = {"f32": 0, "f16": 1, "i8": 2}[dtype]
+    code = {"f32": 0, "f16": 1, "i8": 2, "bf16": 3}[dtype]
     rows = np.ascontiguousarray(rows, dtype=np.int64)
     cols = np.ascontiguousarray(cols, dtype=np.int64)
     out = np.zeros(rows.size, dtype=np.float64)

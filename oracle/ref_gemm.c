@@ -26,7 +26,8 @@
  * Pins (tests/test_oracle_pins.py): exact rational brute force on 7x5x3,
  * identity and permutation operands, all-ones and rank-1 closed forms,
  * small-integer exactness, int8 extremes, all 65536 binary16 patterns against
- * numpy's float16, and torch.matmul in float64/int64 on random inputs.
+ * numpy's float16, all 65536 bfloat16 patterns against the fp32 whose upper
+ * half they are, and torch.matmul in float64/int64 on random inputs.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -60,6 +61,24 @@ double ref_half_to_double(uint16_t h)
         }
     } else {
         v = ldexp((double)(1024 + f), e - 25);          /* (1024+f) * 2^(e-25) */
+    }
+    return sign ? -v : v;
+}
+
+/* bfloat16 bit pattern -> double, exactly (1 sign, 8 exponent, 7 fraction bits; the exponent
+ * range and bias of IEEE binary32). */
+double ref_bfloat16_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 7) & 0xff;
+    int f = h & 0x7f;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -133);                     /* subnormal: f * 2^-7 * 2^-126 */
+    } else if (e == 255) {
+        v = (f == 0) ? 1.0 / 0.0 : 0.0 / 0.0;
+    } else {
+        v = ldexp((double)(128 + f), e - 134);          /* (1 + f/128) * 2^(e-127) */
     }
     return sign ? -v : v;
 }
@@ -118,6 +137,29 @@ int ref_gemm_f16(int layout, int64_t M, int64_t N, int64_t K,
     return 0;
 }
 
+/* bfloat16 inputs (bit patterns), double accumulation, fp32 C in, double result. */
+int ref_gemm_bf16(int layout, int64_t M, int64_t N, int64_t K,
+                  float alpha, const uint16_t *A, int64_t lda,
+                  const uint16_t *B, int64_t ldb,
+                  float beta, const float *C, int64_t ldc,
+                  double *D, int64_t ldd)
+{
+    if (layout != 0 && layout != 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        for (int64_t i = 0; i < M; ++i) {
+            double acc = 0.0;
+            for (int64_t p = 0; p < K; ++p)
+                acc += ref_bfloat16_to_double(A[at(layout, i, p, lda)]) *
+                       ref_bfloat16_to_double(B[at(layout, p, j, ldb)]);
+            double r = (double)alpha * acc;
+            if (beta != 0.0f) r += (double)beta * (double)C[at(layout, i, j, ldc)];
+            D[at(layout, i, j, ldd)] = r;
+        }
+    }
+    return 0;
+}
+
 /* int8 inputs, int64 accumulation; D holds the exact int64 value of
  * alpha*sum + beta*C (the caller wraps it to int32 where it wants to). */
 int ref_gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
@@ -145,7 +187,7 @@ int ref_gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
  * The same definition evaluated only at listed positions (is[s], js[s]), for
  * sizes where the full triple loop would take hours: out[s] = the wide value
  * of C(is[s], js[s]).  dtype: 0 = fp32, 1 = binary16, 2 = int8 (out then holds
- * the int64 result converted to double, exact below 2^53).
+ * the int64 result converted to double, exact below 2^53), 3 = bfloat16.
  */
 int ref_gemm_sample(int dtype, int layout, int64_t K,
                     double alpha, const void *A, int64_t lda,
@@ -154,7 +196,7 @@ int ref_gemm_sample(int dtype, int layout, int64_t K,
                     int64_t nsamp, const int64_t *is, const int64_t *js, double *out)
 {
     if (layout != 0 && layout != 1) return -1;
-    if (dtype < 0 || dtype > 2) return -2;
+    if (dtype < 0 || dtype > 3) return -2;
 #pragma omp parallel for schedule(static)
     for (int64_t s = 0; s < nsamp; ++s) {
         int64_t i = is[s], j = js[s];
@@ -173,11 +215,16 @@ int ref_gemm_sample(int dtype, int layout, int64_t K,
                 const float *a = (const float *)A, *b = (const float *)B;
                 for (int64_t p = 0; p < K; ++p)
                     acc += (double)a[at(layout, i, p, lda)] * (double)b[at(layout, p, j, ldb)];
-            } else {
+            } else if (dtype == 1) {
                 const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
                 for (int64_t p = 0; p < K; ++p)
                     acc += ref_half_to_double(a[at(layout, i, p, lda)]) *
                            ref_half_to_double(b[at(layout, p, j, ldb)]);
+            } else {
+                const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+                for (int64_t p = 0; p < K; ++p)
+                    acc += ref_bfloat16_to_double(a[at(layout, i, p, lda)]) *
+                           ref_bfloat16_to_double(b[at(layout, p, j, ldb)]);
             }
             r = alpha * acc;
             if (beta != 0.0) r += beta * (double)((const float *)C)[at(layout, i, j, ldc)];

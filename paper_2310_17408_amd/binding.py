@@ -11,7 +11,7 @@ import ctypes
 import os
 
 COL_MAJOR, ROW_MAJOR = 0, 1
-F32, F16, I8 = 0, 1, 2
+F32, F16, I8, BF16 = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmi_gemm.so")
@@ -38,7 +38,8 @@ def load():
         _build.build(force=True)
     lib = ctypes.CDLL(_LIB_PATH)
     i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
-    for name, scal in (("gemm_f32", ctypes.c_float), ("gemm_f16", ctypes.c_float), ("gemm_i8", ctypes.c_int32)):
+    for name, scal in (("gemm_f32", ctypes.c_float), ("gemm_f16", ctypes.c_float), ("gemm_bf16", ctypes.c_float),
+                       ("gemm_i8", ctypes.c_int32)):
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [ci, i64, i64, i64, scal, vp, i64, vp, i64, scal, vp, i64, vp, sz, vp]
@@ -105,6 +106,10 @@ def gemm_f32(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=Non
 
 def gemm_f16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
     return _call("gemm_f16", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def gemm_bf16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    return _call("gemm_bf16", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
 
 
 def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):

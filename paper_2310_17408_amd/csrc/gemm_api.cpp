@@ -18,7 +18,8 @@ constexpr int NUM_CU = 256;      // MI355X compute units
 constexpr int MAX_SPLIT = 32;    // upper limit of the K split
 
 struct Forced { int id = -1; int split = 0; };
-Forced g_forced[3];
+constexpr int NUM_DTYPES = 4;
+Forced g_forced[NUM_DTYPES];
 thread_local int t_last_id = -1;
 thread_local int t_last_split = 0;
 
@@ -50,7 +51,7 @@ struct Choice { int id; int split; int ktiles_per_split; };
 // (solo mode on random data), 14 TB/s from L2 into LDS for GEMM-like tile streams, 4 TB/s for the
 // partial-tile round trip, 2.5 us per launch, 3.0 us for the second launch.
 // ---------------------------------------------------------------------------
-constexpr double kSustainedTflops[3] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61};
+constexpr double kSustainedTflops[NUM_DTYPES] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61, 2516.6 * 0.58};
 constexpr double kStagingBytesPerUs = 14.0e6;
 constexpr double kStepFloorUs = 0.75;
 constexpr double kGuardedStepFactor = 2.2;
@@ -61,7 +62,7 @@ constexpr int NUM_SIMD = 4 * NUM_CU;
 
 double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split, bool aligned = true)
 {
-    static const int es[3] = {4, 2, 1};
+    static const int es[NUM_DTYPES] = {4, 2, 1, 2};
     const double tiles = (double)(ceil_div(M, ki->BM) * ceil_div(N, ki->BN));
     const double ktiles = (double)ceil_div(K, ki->BK);
     const double steps = (double)ceil_div((int64_t)ktiles, split);
@@ -268,6 +269,14 @@ int gemm_f16(int layout, int64_t M, int64_t N, int64_t K, float alpha, const uin
                beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream);
 }
 
+int gemm_bf16(int layout, int64_t M, int64_t N, int64_t K, float alpha, const uint16_t *A, int64_t lda,
+              const uint16_t *B, int64_t ldb, float beta, float *C, int64_t ldc, void *workspace,
+              size_t workspace_bytes, void *stream)
+{
+    return run(MI_GEMM_BF16, 2, layout, M, N, K, bits_of(alpha), alpha == 0.0f, A, lda, B, ldb, bits_of(beta),
+               beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream);
+}
+
 int gemm_i8(int layout, int64_t M, int64_t N, int64_t K, int32_t alpha, const int8_t *A, int64_t lda, const int8_t *B,
             int64_t ldb, int32_t beta, int32_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -277,7 +286,7 @@ int gemm_i8(int layout, int64_t M, int64_t N, int64_t K, int32_t alpha, const in
 
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
 {
-    if (dtype < 0 || dtype > 2 || M <= 0 || N <= 0 || K <= 0) return 0;
+    if (dtype < 0 || dtype >= NUM_DTYPES || M <= 0 || N <= 0 || K <= 0) return 0;
     if (M > INT_MAX || N > INT_MAX || K > INT_MAX) return 0;
     // the largest split the model would give any configuration, in either orientation (a
     // row-major call runs the transposed problem)
@@ -311,17 +320,17 @@ const char *gemm_status_string(int status)
     return "unknown status";
 }
 
-int gemm_kernel_count(int dtype) { return (dtype >= 0 && dtype <= 2) ? kernel_count(dtype) : 0; }
+int gemm_kernel_count(int dtype) { return (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_count(dtype) : 0; }
 
 const char *gemm_kernel_name(int dtype, int id)
 {
-    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    const KernelInfo *ki = (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_info(dtype, id) : nullptr;
     return ki ? ki->name : "";
 }
 
 int gemm_force_kernel(int dtype, int id, int split)
 {
-    if (dtype < 0 || dtype > 2) return -1;
+    if (dtype < 0 || dtype >= NUM_DTYPES) return -1;
     if (id < -1 || id >= kernel_count(dtype)) return -1;
     g_forced[dtype].id = id;
     g_forced[dtype].split = split > 0 ? split : 0;
@@ -330,7 +339,7 @@ int gemm_force_kernel(int dtype, int id, int split)
 
 int gemm_kernel_tile(int dtype, int id, int *bm, int *bn, int *bk, int *workgroups_per_cu)
 {
-    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    const KernelInfo *ki = (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_info(dtype, id) : nullptr;
     if (!ki) return -1;
     if (bm) *bm = ki->BM;
     if (bn) *bn = ki->BN;
@@ -342,7 +351,7 @@ int gemm_kernel_tile(int dtype, int id, int *bm, int *bn, int *bk, int *workgrou
 int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int *kernel_id,
                 int *split)
 {
-    if (dtype < 0 || dtype > 2) return -1;
+    if (dtype < 0 || dtype >= NUM_DTYPES) return -1;
     if (layout != MI_GEMM_COL_MAJOR && layout != MI_GEMM_ROW_MAJOR) return -2;
     if (M <= 0 || M > INT_MAX) return -3;
     if (N <= 0 || N > INT_MAX) return -4;
@@ -350,7 +359,7 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
     const bool col = (layout == MI_GEMM_COL_MAJOR);
     // tight leading dimensions and 16-byte aligned base addresses: canonical A has M' contiguous,
     // canonical B has K contiguous
-    static const int es[3] = {4, 2, 1};
+    static const int es[NUM_DTYPES] = {4, 2, 1, 2};
     const int64_t Mc = col ? M : N, Nc = col ? N : M;
     const bool aligned = (Mc * es[dtype]) % 16 == 0 && (K * es[dtype]) % 16 == 0;
     const Choice ch = choose(dtype, Mc, Nc, K, Mc, K, workspace_bytes, workspace_bytes > 0, aligned);
@@ -361,15 +370,15 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
 
 double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int split)
 {
-    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
+    const KernelInfo *ki = (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_info(dtype, id) : nullptr;
     if (!ki || M <= 0 || N <= 0 || K <= 0 || split <= 0 || M > INT_MAX || N > INT_MAX || K > INT_MAX) return -1.0;
     return predict_us(dtype, ki, M, N, K, split);
 }
 
 int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *stream)
 {
-    const KernelInfo *ki = (dtype >= 0 && dtype <= 2) ? kernel_info(dtype, id) : nullptr;
-    if (!ki) return dtype < 0 || dtype > 2 ? -1 : -2;
+    const KernelInfo *ki = (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_info(dtype, id) : nullptr;
+    if (!ki) return dtype < 0 || dtype >= NUM_DTYPES ? -1 : -2;
     if (workgroups < 1 || workgroups > (1 << 20)) return -3;
     if (ksteps < 0) return -4;
     if (fill != 0 && fill != 1) return -5;

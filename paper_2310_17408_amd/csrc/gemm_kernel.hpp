@@ -34,6 +34,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 // the same vectors at element alignment only: gfx950 serves global loads at any alignment
 // (the amdhsa target runs with unaligned access enabled), at the price of a second cache access
 // when a load straddles a line
@@ -50,6 +51,13 @@ struct F32 {
     static constexpr int KCH = 4;   // K elements per 16-byte chunk
 };
 struct F16 {
+    typedef uint16_t elt;
+    typedef float acc_t;
+    typedef v16f accv;
+    static constexpr int ES = 2;
+    static constexpr int KCH = 8;
+};
+struct BF16 {          // bfloat16 bit patterns in, fp32 accumulation; laid out like F16 everywhere
     typedef uint16_t elt;
     typedef float acc_t;
     typedef v16f accv;
@@ -84,6 +92,12 @@ template <> struct Mma<F16> {
                                                    __builtin_bit_cast(v8h, colop), c, 0, 0, 0);
     }
 };
+template <> struct Mma<BF16> {
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v16f &c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, rowop),
+                                                    __builtin_bit_cast(v8bf, colop), c, 0, 0, 0);
+    }
+};
 template <> struct Mma<I8> {
     static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v16i &c) {
         c = __builtin_amdgcn_mfma_i32_32x32x32_i8(rowop, colop, c, 0, 0, 0);
@@ -115,6 +129,8 @@ template <int MB> struct Transpose<F16, MB> {     // MB = 2, 4 or 8
         return o;
     }
 };
+
+template <int MB> struct Transpose<BF16, MB> : Transpose<F16, MB> {};   // 16-bit elements move alike
 
 __device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
     return __builtin_amdgcn_perm(hi, lo, sel);   // bytes 0-3 index lo, 4-7 index hi

@@ -55,7 +55,7 @@ struct KernelInfo {
     int unaligned_pct;
 };
 
-int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8
+int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8, 3 bf16
 const KernelInfo *kernel_info(int dtype, int id);  // nullptr if out of range
 
 hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,

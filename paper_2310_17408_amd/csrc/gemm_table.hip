@@ -145,6 +145,9 @@ typedef Tile<F32, 64, 64, 2, 2, 2, 2> F32_64x64;
 typedef Tile<F16, 256, 256, 2, 2, 8, 1> F16_256x256;
 typedef Tile<F16, 128, 128, 2, 2, 8, 2> F16_128x128;
 typedef Tile<F16, 64, 64, 2, 2, 2, 2> F16_64x64;
+typedef Tile<BF16, 256, 256, 2, 2, 8, 1> BF16_256x256;
+typedef Tile<BF16, 128, 128, 2, 2, 8, 2> BF16_128x128;
+typedef Tile<BF16, 64, 64, 2, 2, 2, 2> BF16_64x64;
 typedef Tile<I8, 256, 256, 2, 2, 8, 1> I8_256x256;
 typedef Tile<I8, 128, 128, 2, 2, 4, 2> I8_128x128;
 typedef Tile<I8, 64, 64, 2, 2, 4, 2> I8_64x64;
@@ -175,6 +178,13 @@ static const KernelInfo k_f16[] = {
     info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 1, 72, 880, 1500),
     info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 1, 82, 1800, 1500),
 };
+static const KernelInfo k_bf16[] = {
+    info<BF16_256x256>("bf16_256x256_w128x128", 0, 50, 2500, 1500),
+    info<BF16_128x128>("bf16_128x128_w64x64", 0, 47, 1700, 1500),
+    info<BF16_64x64>("bf16_64x64_w32x32", 1, 40, 600, 1500),
+    info_dma<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma", 1, 72, 880, 1500),
+    info_dma<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma", 1, 82, 1800, 1500),
+};
 static const KernelInfo k_i8[] = {
     info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500, 1500),
     info<I8_128x128>("i8_128x128_w64x64", 0, 47, 800, 1500),
@@ -189,6 +199,7 @@ int kernel_count(int dtype)
     case 0: return (int)(sizeof(k_f32) / sizeof(k_f32[0]));
     case 1: return (int)(sizeof(k_f16) / sizeof(k_f16[0]));
     case 2: return (int)(sizeof(k_i8) / sizeof(k_i8[0]));
+    case 3: return (int)(sizeof(k_bf16) / sizeof(k_bf16[0]));
     default: return 0;
     }
 }
@@ -196,7 +207,7 @@ int kernel_count(int dtype)
 const KernelInfo *kernel_info(int dtype, int id)
 {
     if (id < 0 || id >= kernel_count(dtype)) return nullptr;
-    return dtype == 0 ? &k_f32[id] : dtype == 1 ? &k_f16[id] : &k_i8[id];
+    return dtype == 0 ? &k_f32[id] : dtype == 1 ? &k_f16[id] : dtype == 2 ? &k_i8[id] : &k_bf16[id];
 }
 
 static unsigned blocks_for(int64_t total)

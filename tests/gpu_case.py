@@ -8,9 +8,11 @@ import oracle
 import workloads as wl
 import paper_2310_17408_amd as mg
 
-DT = {"f32": mg.F32, "f16": mg.F16, "i8": mg.I8}
+DT = {"f32": mg.F32, "f16": mg.F16, "i8": mg.I8, "bf16": mg.BF16}
 LAYOUT = {"col": mg.COL_MAJOR, "row": mg.ROW_MAJOR}
-TOL = {"f32": 1e-6, "f16": 2e-3}          # max|C - C_ref| / (K max|A| max|B|)
+# max|C - C_ref| / (K max|A| max|B|); bfloat16 inputs take the bar of the other 16-bit format: their
+# products are exact in fp32 as well, so the error is that of the fp32 accumulation alone
+TOL = {"f32": 1e-6, "f16": 2e-3, "bf16": 2e-3}
 
 
 def make_inputs(dtype, layout, M, N, K, seed, pad=(0, 0, 0), values="random"):
@@ -23,6 +25,10 @@ def make_inputs(dtype, layout, M, N, K, seed, pad=(0, 0, 0), values="random"):
         C = gen(seed + 2, layout, M, N, ldc)
     elif dtype == "f16":
         gen = wl.small_int_f16_bits if values == "smallint" else wl.normal_f16_bits
+        A, B = gen(seed, layout, M, K, lda), gen(seed + 1, layout, K, N, ldb)
+        C = (wl.small_int_f32 if values == "smallint" else wl.uniform_f32)(seed + 2, layout, M, N, ldc)
+    elif dtype == "bf16":
+        gen = wl.small_int_bf16_bits if values == "smallint" else wl.normal_bf16_bits
         A, B = gen(seed, layout, M, K, lda), gen(seed + 1, layout, K, N, ldb)
         C = (wl.small_int_f32 if values == "smallint" else wl.uniform_f32)(seed + 2, layout, M, N, ldc)
     else:
@@ -43,14 +49,18 @@ def to_device(host, offset_elems=0):
 
 
 def max_abs(dtype, layout, buf, rows, cols):
-    x = wl.logical(layout, buf.view(np.float16) if dtype == "f16" else buf, rows, cols)
+    if dtype == "f16":
+        buf = buf.view(np.float16)
+    elif dtype == "bf16":
+        buf = wl.bf16_bits_to_f32(buf)
+    x = wl.logical(layout, buf, rows, cols)
     return float(np.max(np.abs(x.astype(np.float64)))) if x.size else 0.0
 
 
 def gpu_gemm(dtype, layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, kernel_id=-1, split=0,
              workspace_bytes=None, offsets=(0, 0, 0)):
     """Run the library on host arrays; returns (C buffer after the call as numpy, kernel id, split)."""
-    fn = {"f32": mg.gemm_f32, "f16": mg.gemm_f16, "i8": mg.gemm_i8}[dtype]
+    fn = {"f32": mg.gemm_f32, "f16": mg.gemm_f16, "i8": mg.gemm_i8, "bf16": mg.gemm_bf16}[dtype]
     _, dA = to_device(A, offsets[0])
     _, dB = to_device(B, offsets[1])
     _, dC = to_device(C, offsets[2])
@@ -71,7 +81,7 @@ def gpu_gemm(dtype, layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, kernel
 
 
 def oracle_gemm(dtype, layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
-    fn = {"f32": oracle.gemm_f32, "f16": oracle.gemm_f16, "i8": oracle.gemm_i8}[dtype]
+    fn = {"f32": oracle.gemm_f32, "f16": oracle.gemm_f16, "i8": oracle.gemm_i8, "bf16": oracle.gemm_bf16}[dtype]
     return fn(layout, M, N, K, alpha, A, lda, B, ldb, beta, C if beta != 0 else None, ldc)
 
 

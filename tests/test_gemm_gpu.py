@@ -16,7 +16,7 @@ from gpu_case import DT, LAYOUT, check_case, gpu_gemm, make_inputs, oracle_gemm,
 
 pytestmark = pytest.mark.gpu
 
-DTYPES = ["f32", "f16", "i8"]
+DTYPES = ["f32", "f16", "i8", "bf16"]
 LAYOUTS = ["col", "row"]
 
 
@@ -104,7 +104,7 @@ def test_split_k_invariance_int8_and_determinism():
 
 
 # ------------------------------------------------------------ exact regimes
-@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("alpha,beta", [(1, 0), (2, -1), (0.5, 1), (-1, 2)])
 def test_small_integer_inputs_exact(dtype, layout, alpha, beta):

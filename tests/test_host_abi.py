@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_kernel_table():
-    for dtype in (mg.F32, mg.F16, mg.I8):
+    for dtype in (mg.F32, mg.F16, mg.I8, mg.BF16):
         n = mg.gemm_kernel_count(dtype)
         assert n >= 3
         names = [mg.gemm_kernel_name(dtype, i) for i in range(n)]
@@ -41,7 +41,7 @@ def test_kernel_table():
     assert mg.gemm_force_kernel(5, 0, 0) == -1
 
 
-@pytest.mark.parametrize("fn", [mg.gemm_f32, mg.gemm_f16, mg.gemm_i8])
+@pytest.mark.parametrize("fn", [mg.gemm_f32, mg.gemm_f16, mg.gemm_i8, mg.gemm_bf16])
 def test_argument_errors_return_before_any_launch(fn):
     P = 0x1000            # never dereferenced: every call below fails validation or returns early
     ok = dict(layout=mg.COL_MAJOR, M=8, N=9, K=10, alpha=1, A=P, lda=8, B=P, ldb=10, beta=0, C=P, ldc=8)
@@ -106,7 +106,7 @@ def test_timing_model_and_selection_agree():
     """gemm_select returns the (configuration, split) with the smallest predicted time among the
     configurations open to automatic selection, and the model behaves sanely: more work never
     takes less time, bad arguments are refused."""
-    for dtype in (mg.F32, mg.F16, mg.I8):
+    for dtype in (mg.F32, mg.F16, mg.I8, mg.BF16):
         for (M, N, K) in [(12544, 64, 147), (49, 512, 4608), (1024, 1024, 1024), (4096, 4096, 4096), (33, 17, 2049)]:
             kid, split = mg.gemm_select(dtype, 0, M, N, K, 32 * M * N * 4)
             t = mg.gemm_predict_us(dtype, kid, M, N, K, split)

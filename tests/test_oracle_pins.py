@@ -351,3 +351,71 @@ def test_metric_distinguishes_fp16_accumulation():
         acc32 = acc32 + prod
     assert oracle.normalised_error(acc32, D, K, max_a, max_b) < 1e-7
     assert oracle.normalised_error(acc16, D, K, max_a, max_b) > 1e-5
+
+
+# ---------------------------------------------------------------- bfloat16
+def test_bfloat16_decode_all_patterns():
+    """A bfloat16 is the upper half of an IEEE binary32: every pattern against numpy's float32."""
+    bits = np.arange(65536, dtype=np.uint16)
+    with np.errstate(invalid="ignore"):      # signalling NaN patterns are among the 65536
+        want = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    got = np.array([oracle.bfloat16_to_double(b) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_bfloat16_generator_rounds_to_nearest_even():
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -7, -2.5, 3.0e38, 1.0 + 2.0 ** -8 + 2.0 ** -20],
+                 dtype=np.float32)
+    got = wl.bf16_bits_to_f32(wl._to_bf16_bits(x))
+    # ties go to the even significand: 1 + 2^-8 -> 1, 1 + 3*2^-8 -> 1 + 2^-6; above a tie rounds up
+    assert got.tolist() == [1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -2.5, 226 * 2.0 ** 120,
+                            1.0 + 2.0 ** -7]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_bf16_small_exact_rational_and_library(layout):
+    M, N, K = 5, 6, 4
+    lda = wl.tight_ld(layout, M, K) + 1
+    ldb = wl.tight_ld(layout, K, N) + 2
+    ldc = wl.tight_ld(layout, M, N) + 3
+    A = wl.normal_bf16_bits(61, layout, M, K, lda)
+    B = wl.normal_bf16_bits(62, layout, K, N, ldb)
+    C = wl.uniform_f32(63, layout, M, N, ldc)
+    D = oracle.gemm_bf16(layout, M, N, K, 1.0, A, lda, B, ldb, 0.0, None, 0)
+    Af, Bf = wl.bf16_bits_to_f32(A), wl.bf16_bits_to_f32(B)
+    for i in range(M):
+        for j in range(N):
+            s = Fraction(0)
+            for p in range(K):
+                s += Fraction(float(_get(layout, Af, i, p, lda))) * Fraction(float(_get(layout, Bf, p, j, ldb)))
+            # bfloat16 products have 16-bit significands; a 4-term sum of N(0,1)-sized ones is exact in fp64
+            assert Fraction(float(D[i, j])) == s
+    # alpha, beta and a library second opinion in float64
+    M, N, K = 33, 17, 129
+    lda, ldb, ldc = wl.tight_ld(layout, M, K) + 3, wl.tight_ld(layout, K, N) + 5, wl.tight_ld(layout, M, N) + 1
+    A, B = wl.normal_bf16_bits(64, layout, M, K, lda), wl.normal_bf16_bits(65, layout, K, N, ldb)
+    C = wl.uniform_f32(66, layout, M, N, ldc)
+    D = oracle.gemm_bf16(layout, M, N, K, np.float32(1.5), A, lda, B, ldb, np.float32(0.5), C, ldc)
+    tA = torch.from_numpy(wl.logical(layout, wl.bf16_bits_to_f32(A), M, K).astype(np.float64))
+    tB = torch.from_numpy(wl.logical(layout, wl.bf16_bits_to_f32(B), K, N).astype(np.float64))
+    tC = torch.from_numpy(wl.logical(layout, C, M, N).astype(np.float64))
+    want = (1.5 * (tA @ tB) + 0.5 * tC).numpy()
+    scale = float(tA.abs().max() * tB.abs().max())
+    assert np.max(np.abs(D - want)) <= (K + 2) * 2.0 ** -52 * K * max(scale, 1.0) * 2
+    # sampled evaluation agrees with the full one
+    rows, cols = np.array([0, 5, 32, 7]), np.array([0, 16, 3, 9])
+    samp = oracle.gemm_sample("bf16", layout, K, 1.5, A, lda, B, ldb, 0.5, C, ldc, rows, cols)
+    assert np.array_equal(samp, D[rows, cols])
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_bf16_small_integers_match_fp32_oracle(layout):
+    M, N, K = 17, 9, 130
+    lda, ldb, ldc = wl.tight_ld(layout, M, K), wl.tight_ld(layout, K, N), wl.tight_ld(layout, M, N)
+    A, B, C = wl.small_int_f32(41, layout, M, K), wl.small_int_f32(42, layout, K, N), wl.small_int_f32(43, layout, M, N)
+    D = oracle.gemm_f32(layout, M, N, K, 2.0, A, lda, B, ldb, -1.0, C, ldc)
+    Db = oracle.gemm_bf16(layout, M, N, K, 2.0, wl._to_bf16_bits(A), lda, wl._to_bf16_bits(B), ldb, -1.0, C, ldc)
+    assert np.array_equal(Db, D)

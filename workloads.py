@@ -69,6 +69,18 @@ def normal_f16_bits(seed, layout, rows, cols, ld=None):
     return np.ascontiguousarray(x.astype(np.float16).view(np.uint16))
 
 
+def _to_bf16_bits(x):
+    """float32 array -> bfloat16 bit patterns (the upper 16 bits), rounded to nearest, ties to even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    return ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+
+
+def normal_bf16_bits(seed, layout, rows, cols, ld=None):
+    """rows x cols matrix of N(0,1) draws rounded to bfloat16, returned as uint16 bit patterns."""
+    ld = tight_ld(layout, rows, cols) if ld is None else ld
+    return _to_bf16_bits(_rng(seed).standard_normal(_shape(layout, rows, cols, ld), dtype=np.float32))
+
+
 def uniform_i8(seed, layout, rows, cols, ld=None):
     """rows x cols int8 matrix, entries uniform on [-128, 127]."""
     ld = tight_ld(layout, rows, cols) if ld is None else ld
@@ -90,6 +102,17 @@ def small_int_f16_bits(seed, layout, rows, cols, ld=None, bound=8):
     ld = tight_ld(layout, rows, cols) if ld is None else ld
     x = _rng(seed).integers(-bound, bound + 1, size=_shape(layout, rows, cols, ld)).astype(np.float16)
     return np.ascontiguousarray(x.view(np.uint16))
+
+
+def small_int_bf16_bits(seed, layout, rows, cols, ld=None, bound=8):
+    ld = tight_ld(layout, rows, cols) if ld is None else ld
+    x = _rng(seed).integers(-bound, bound + 1, size=_shape(layout, rows, cols, ld)).astype(np.float32)
+    return _to_bf16_bits(x)          # small integers are bfloat16 values already
+
+
+def bf16_bits_to_f32(bits):
+    """bfloat16 bit patterns -> the float32 values they denote."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
 def logical(layout, buf, rows, cols):
