@@ -98,6 +98,24 @@ int gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
             int32_t beta, int32_t *C, int64_t ldc,
             void *workspace, size_t workspace_bytes, void *stream);
 
+/* The general form C = alpha*op(A)*op(B) + beta*C for any data type, op(X) = X
+ * (trans = 0) or X^T (trans = 1): op(A) is M x K and op(B) is K x N, so a
+ * transposed A is stored as a K x M matrix and a transposed B as N x K, in the
+ * layout given (column-major: X(i,j) at X[i + j*ldx], row-major: X[i*ldx + j]),
+ * with lda / ldb at least the contiguous extent of the stored matrix.  This is
+ * the transposed-operand case the paper's Sec. "Micro-kernel Generation" sets
+ * aside when it fixes row-major C code with C^T = B^T A^T.  alpha and beta are
+ * host pointers to a float (fp32, fp16, bf16) or an int32 (int8).  With
+ * transa = transb = 0 the call is gemm_f32 / gemm_f16 / gemm_i8 / gemm_bf16;
+ * transposed operands run on the staged kernels.  Same ownership, stream and
+ * workspace rules; status -k names the k-th argument of this list
+ * (gemm_ex_status_string gives the text). */
+int gemm_ex(int dtype, int layout, int transa, int transb, int64_t M, int64_t N, int64_t K,
+            const void *alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+            const void *beta, void *C, int64_t ldc,
+            void *workspace, size_t workspace_bytes, void *stream);
+const char *gemm_ex_status_string(int status);
+
 /* Upper bound of the workspace any split of the K loop may use for this
  * problem (dtype is one of MI_GEMM_F32/F16/I8/BF16); 0 if M, N or K is not positive. */
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K);

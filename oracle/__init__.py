@@ -19,6 +19,7 @@ from .ref import (  # noqa: F401
     gemm_f16,
     gemm_bf16,
     gemm_i8,
+    gemm_ex,
     gemm_sample,
     wrap_int32,
     normalised_error,

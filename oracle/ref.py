@@ -42,6 +42,8 @@ def _load():
             fn = getattr(lib, name)
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_int, i64, i64, i64, scal, vp, i64, vp, i64, scal, vp, i64, vp, i64]
+        lib.ref_gemm_ex.restype = ctypes.c_int
+        lib.ref_gemm_ex.argtypes = [ctypes.c_int] * 4 + [i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, vp, i64]
         lib.ref_gemm_sample.restype = ctypes.c_int
         lib.ref_gemm_sample.argtypes = [ctypes.c_int, ctypes.c_int, i64, dbl, vp, i64, vp, i64,
                                         dbl, vp, i64, i64, vp, vp, vp]
@@ -126,6 +128,28 @@ def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
     """int8 inputs, int32 C in; returns the exact int64 result (M, N)."""
     return _run(_load().ref_gemm_i8, np.int8, np.int32, np.int64,
                 layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc)
+
+
+def gemm_ex(dtype, layout, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc):
+    """C = alpha*op(A)*op(B) + beta*C with op(X) = X^T where the flag is set; dtype is "f32", "f16",
+    "bf16" or "i8".  Returns the wide result (double, or int64 for int8) as an (M, N) array."""
+    code = {"f32": 0, "f16": 1, "i8": 2, "bf16": 3}[dtype]
+    in_dtype = {"f32": np.float32, "f16": np.uint16, "bf16": np.uint16, "i8": np.int8}[dtype]
+    ar, ac = (K, M) if transa else (M, K)
+    br, bc = (N, K) if transb else (K, N)
+    _check("A", A, in_dtype, layout, ar, ac, lda)
+    _check("B", B, in_dtype, layout, br, bc, ldb)
+    _check("C", C, np.int32 if dtype == "i8" else np.float32, layout, M, N, ldc)
+    if C is None and beta != 0:
+        raise ValueError("beta != 0 needs C")
+    ldd = max(1, M if layout == "col" else N)
+    D = np.zeros((N, M) if layout == "col" else (M, N), dtype=np.int64 if dtype == "i8" else np.float64)
+    rc = _load().ref_gemm_ex(code, _LAYOUT[layout], int(bool(transa)), int(bool(transb)), M, N, K, float(alpha),
+                             _ptr(A), lda, _ptr(B), ldb, float(beta), _ptr(C), ldc if C is not None else ldd,
+                             _ptr(D), ldd)
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    return D.T if layout == "col" else D
 
 
 def gemm_sample(dtype, layout, K, alpha, A, lda, B, ldb, beta, C, ldc, rows, cols):

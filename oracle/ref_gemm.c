@@ -184,6 +184,60 @@ int ref_gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
 }
 
 /*
+ * The general form C = alpha*op(A)*op(B) + beta*C, op(X) = X or X^T (BLAS
+ * convention: op(A) is M x K, op(B) is K x N; a transposed operand is stored
+ * as the K x M, respectively N x K, matrix in the given layout).  Element
+ * (i,j) of op(X) is element (j,i) of the stored X when X is transposed.
+ * dtype: 0 = fp32, 1 = binary16, 3 = bfloat16 (D is double), 2 = int8 (D is
+ * int64, alpha and beta are converted to int64).
+ */
+static inline size_t at_op(int layout, int trans, int64_t i, int64_t j, int64_t ld)
+{
+    return trans ? at(layout, j, i, ld) : at(layout, i, j, ld);
+}
+
+static inline double wide_elem(int dtype, const void *X, size_t idx)
+{
+    switch (dtype) {
+    case 0: return (double)((const float *)X)[idx];
+    case 1: return ref_half_to_double(((const uint16_t *)X)[idx]);
+    case 3: return ref_bfloat16_to_double(((const uint16_t *)X)[idx]);
+    default: return (double)((const int8_t *)X)[idx];
+    }
+}
+
+int ref_gemm_ex(int dtype, int layout, int transa, int transb, int64_t M, int64_t N, int64_t K,
+                double alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                double beta, const void *C, int64_t ldc, void *D, int64_t ldd)
+{
+    if (layout != 0 && layout != 1) return -1;
+    if (dtype < 0 || dtype > 3) return -2;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        for (int64_t i = 0; i < M; ++i) {
+            if (dtype == 2) {
+                const int8_t *a = (const int8_t *)A, *b = (const int8_t *)B;
+                int64_t acc = 0;
+                for (int64_t p = 0; p < K; ++p)
+                    acc += (int64_t)a[at_op(layout, transa, i, p, lda)] * (int64_t)b[at_op(layout, transb, p, j, ldb)];
+                int64_t r = (int64_t)alpha * acc;
+                if (beta != 0.0) r += (int64_t)beta * (int64_t)((const int32_t *)C)[at(layout, i, j, ldc)];
+                ((int64_t *)D)[at(layout, i, j, ldd)] = r;
+            } else {
+                double acc = 0.0;
+                for (int64_t p = 0; p < K; ++p)
+                    acc += wide_elem(dtype, A, at_op(layout, transa, i, p, lda)) *
+                           wide_elem(dtype, B, at_op(layout, transb, p, j, ldb));
+                double r = alpha * acc;
+                if (beta != 0.0) r += beta * (double)((const float *)C)[at(layout, i, j, ldc)];
+                ((double *)D)[at(layout, i, j, ldd)] = r;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
  * The same definition evaluated only at listed positions (is[s], js[s]), for
  * sizes where the full triple loop would take hours: out[s] = the wide value
  * of C(is[s], js[s]).  dtype: 0 = fp32, 1 = binary16, 2 = int8 (out then holds

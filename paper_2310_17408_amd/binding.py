@@ -55,6 +55,10 @@ def load():
     lib.gemm_force_kernel.argtypes = [ci, ci, ci]
     lib.gemm_kernel_tile.restype = ci
     lib.gemm_kernel_tile.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 4
+    lib.gemm_ex.restype = ci
+    lib.gemm_ex.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64, vp, sz, vp]
+    lib.gemm_ex_status_string.restype = ctypes.c_char_p
+    lib.gemm_ex_status_string.argtypes = [ci]
     lib.gemm_predict_us.restype = ctypes.c_double
     lib.gemm_predict_us.argtypes = [ci, ci, i64, i64, i64, ci]
     lib.gemm_select.restype = ci
@@ -114,6 +118,20 @@ def gemm_bf16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=No
 
 def gemm_i8(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
     return _call("gemm_i8", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def gemm_ex(dtype, layout, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None,
+            check=True):
+    """C = alpha*op(A)*op(B) + beta*C for any data type; alpha and beta are Python numbers."""
+    lib = load()
+    ws, ws_bytes = _ws(workspace)
+    scal = ctypes.c_int32 if dtype == I8 else ctypes.c_float
+    a, b = scal(alpha), scal(beta)
+    status = lib.gemm_ex(dtype, layout, int(transa), int(transb), M, N, K, ctypes.byref(a), _addr(A), lda, _addr(B), ldb,
+                         ctypes.byref(b), _addr(C), ldc, ws, ws_bytes, _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, lib.gemm_ex_status_string(status).decode())
+    return status
 
 
 def gemm_workspace_bytes(dtype, M, N, K):

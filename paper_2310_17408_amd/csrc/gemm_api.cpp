@@ -129,14 +129,16 @@ bool can_address(const KernelInfo *ki, int64_t lda, int64_t ldb)
 
 // Best (configuration, split) over the configurations open to automatic selection (prio > 0).
 int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t max_split_bytes_per_mn,
-                bool aligned)
+                bool aligned, bool transposed)
 {
     const int n = kernel_count(dtype);
     int best = -1;
     double best_us = 0.0;
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        if (ki->prio <= 0 || !can_address(ki, lda, ldb)) continue;
+        // transposed operands: every configuration that takes them; otherwise those open to selection
+        if (transposed ? !ki->transposed_ok : ki->prio <= 0) continue;
+        if (!can_address(ki, lda, ldb)) continue;
         const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned);
         const double t = predict_us(dtype, ki, M, N, K, s, aligned);
         if (best < 0 || t < best_us) { best = id; best_us = t; }
@@ -145,7 +147,7 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
 }
 
 Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws,
-              bool aligned)
+              bool aligned, bool transposed = false)
 {
     Choice c;
     const Forced f = g_forced[dtype];
@@ -154,8 +156,9 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
     if (fit > MAX_SPLIT) fit = MAX_SPLIT;
     if (fit < 1) fit = 1;
-    const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb);
-    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned);
+    const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb) &&
+                        (!transposed || kernel_info(dtype, f.id)->transposed_ok);
+    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, transposed);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
     int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned);
@@ -173,9 +176,11 @@ bool aligned16(const void *p, int64_t ld, int es)
     return ((uintptr_t)p % 16 == 0) && ((ld * es) % 16 == 0) && (ld * es < ((int64_t)1 << 27));
 }
 
+// Status codes are those of the gemm_f32 / f16 / bf16 / i8 argument list: -k for its k-th argument.
+// transa / transb: op(A) = A^T / op(B) = B^T (gemm_ex only; checked by the caller).
 int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t alpha_bits, bool alpha_zero,
         const void *A, int64_t lda, const void *B, int64_t ldb, uint32_t beta_bits, bool beta_zero, bool beta_one,
-        void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream_)
+        void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream_, bool transa = false, bool transb = false)
 {
     t_last_id = -1;
     t_last_split = 0;
@@ -185,8 +190,11 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     if (K < 0 || K > INT_MAX) return -4;
     const bool col = (layout == MI_GEMM_COL_MAJOR);
     const int64_t one = 1;
-    if (lda < (col ? (M > one ? M : one) : (K > one ? K : one))) return -7;
-    if (ldb < (col ? (K > one ? K : one) : (N > one ? N : one))) return -9;
+    // the stored A is M x K, or K x M when transposed; the stored B is K x N, or N x K; a leading
+    // dimension spans the contiguous extent of the stored matrix
+    const int64_t a_span = (col != transa) ? M : K, b_span = (col != transb) ? K : N;
+    if (lda < (a_span > one ? a_span : one)) return -7;
+    if (ldb < (b_span > one ? b_span : one)) return -9;
     if (ldc < (col ? (M > one ? M : one) : (N > one ? N : one))) return -12;
     if (ws != nullptr && (uintptr_t)ws % 16 != 0) return -13;
     if (M == 0 || N == 0) return 0;
@@ -199,13 +207,16 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
 
     // canonical form: C' column-major M' x N'.  A row-major problem is the
     // column-major problem C^T = B^T A^T on the same buffers.
+    // Canonical A has M' contiguous unless a_kc, canonical B has K contiguous unless b_nc.
     int64_t Mc = M, Nc = N;
     const void *Ac = A, *Bc = B;
     int64_t ldac = lda, ldbc = ldb;
+    bool a_kc = transa, b_nc = transb;
     if (!col) {
         Mc = N; Nc = M;
         Ac = B; ldac = ldb;
         Bc = A; ldbc = lda;
+        a_kc = transb; b_nc = transa;
     }
 
     if (no_product) {
@@ -215,7 +226,7 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     }
 
     const bool vec_a = aligned16(Ac, ldac, es), vec_b = aligned16(Bc, ldbc, es);
-    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr, vec_a && vec_b);
+    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr, vec_a && vec_b, a_kc || b_nc);
     const KernelInfo *ki = kernel_info(dtype, ch.id);
 
     Params p;
@@ -234,6 +245,8 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     p.use_beta = beta_zero ? 0 : 1;
     p.vecA = vec_a ? 1 : 0;
     p.vecB = vec_b ? 1 : 0;
+    p.a_kc = a_kc ? 1 : 0;
+    p.b_nc = b_nc ? 1 : 0;
     p.group_m = 8;
     p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
 
@@ -284,6 +297,32 @@ int gemm_i8(int layout, int64_t M, int64_t N, int64_t K, int32_t alpha, const in
                beta == 1, C, ldc, workspace, workspace_bytes, stream);
 }
 
+int gemm_ex(int dtype, int layout, int transa, int transb, int64_t M, int64_t N, int64_t K, const void *alpha,
+            const void *A, int64_t lda, const void *B, int64_t ldb, const void *beta, void *C, int64_t ldc,
+            void *workspace, size_t workspace_bytes, void *stream)
+{
+    static const int es[NUM_DTYPES] = {4, 2, 1, 2};
+    if (dtype < 0 || dtype >= NUM_DTYPES) return -1;
+    if (transa != 0 && transa != 1) return -3;
+    if (transb != 0 && transb != 1) return -4;
+    if (alpha == nullptr) return -8;
+    if (beta == nullptr) return -13;
+    int rc;
+    if (dtype == MI_GEMM_I8) {
+        const int32_t a = *(const int32_t *)alpha, b = *(const int32_t *)beta;
+        rc = run(dtype, 1, layout, M, N, K, (uint32_t)a, a == 0, A, lda, B, ldb, (uint32_t)b, b == 0, b == 1, C, ldc,
+                 workspace, workspace_bytes, stream, transa != 0, transb != 0);
+    } else {
+        const float a = *(const float *)alpha, b = *(const float *)beta;
+        rc = run(dtype, es[dtype], layout, M, N, K, bits_of(a), a == 0.0f, A, lda, B, ldb, bits_of(b), b == 0.0f,
+                 b == 1.0f, C, ldc, workspace, workspace_bytes, stream, transa != 0, transb != 0);
+    }
+    // run() numbers the arguments of gemm_f32; here layout is the 2nd and M the 5th
+    if (rc == -1) return -2;
+    if (rc < -1) return rc - 3;
+    return rc;
+}
+
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
 {
     if (dtype < 0 || dtype >= NUM_DTYPES || M <= 0 || N <= 0 || K <= 0) return 0;
@@ -318,6 +357,25 @@ const char *gemm_status_string(int status)
     if (status <= 0 && status >= -15) return arg[-status];
     if (status > 0) return hipGetErrorString((hipError_t)status);
     return "unknown status";
+}
+
+const char *gemm_ex_status_string(int status)
+{
+    if (status == -1) return "argument 1 (dtype) is not MI_GEMM_F32, MI_GEMM_F16, MI_GEMM_I8 or MI_GEMM_BF16";
+    if (status == -2) return gemm_status_string(-1);
+    if (status == -3) return "argument 3 (transa) is not 0 or 1";
+    if (status == -4) return "argument 4 (transb) is not 0 or 1";
+    if (status == -8) return "argument 8 (alpha) is NULL";
+    if (status == -13) return "argument 13 (beta) is NULL";
+    if (status <= -5 && status >= -18) {
+        // the same text with the position in gemm_ex's list
+        static thread_local char buf[160];
+        const char *legacy = gemm_status_string(status + 3);
+        const char *paren = strchr(legacy, '(');
+        snprintf(buf, sizeof(buf), "argument %d %s", -status, paren ? paren : legacy);
+        return buf;
+    }
+    return gemm_status_string(status);
 }
 
 int gemm_kernel_count(int dtype) { return (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_count(dtype) : 0; }

@@ -21,6 +21,8 @@
 //   C is M x N column-major, element (m,n) at C[m + n*ldc];
 //   A is M x K with M contiguous, element (m,k) at A[m + k*lda];
 //   B is K x N with K contiguous, element (k,n) at B[k + n*ldb].
+// Transposed operands (this kernel only): A with K contiguous, element (m,k) at A[k + m*lda], and
+// B with N contiguous, element (k,n) at B[n + k*ldb].
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -170,10 +172,6 @@ struct Tile {
     static constexpr int ROWB = 128 + 16;            // LDS bytes per tile row (16 bytes of padding)
     static constexpr int STAGE = (BM + BN) * ROWB;   // one LDS buffer
     static constexpr int LDS_BYTES = 2 * STAGE;      // double buffered
-    static constexpr int A_BLOCKS = (BM / MB) * 8;   // MB x KCH blocks of the A tile
-    static constexpr int A_IT = (A_BLOCKS + NT - 1) / NT;
-    static constexpr int B_CHUNKS = BN * 8;
-    static constexpr int B_IT = (B_CHUNKS + NT - 1) / NT;         // 16-byte chunks of the B tile per lane
     static constexpr int AW = MB * DT::ES / 4;       // 32-bit words per loaded A vector
     static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tiles are made of 32x32 blocks");
 };
@@ -273,17 +271,144 @@ __device__ __forceinline__ void micro_kernel(const unsigned char *stage, int wm0
     }
 }
 
-template <class T>
+// One operand tile of the staged kernel on its way global -> registers -> LDS: ROWS tile rows (m for
+// A, n for B) of BK elements of K.  In memory the operand has either K contiguous (element (r, k) at
+// src[r*ld + k]: the canonical B, or a transposed A) or its rows contiguous (element (r, k) at
+// src[k*ld + r]: the canonical A, or a transposed B); in LDS it always ends up row by row with K
+// contiguous (the packing step), the second kind through the register transposes above.
+template <class T, int ROWS, bool K_CONTIGUOUS>
+struct StagedOperand {
+    typedef typename T::DT DT;
+    typedef typename DT::elt elt;
+    static constexpr int NT = T::NT, ROWB = T::ROWB, BK = T::BK, MB = T::MB, KCH = DT::KCH, ES = DT::ES;
+    static constexpr int AW = T::AW;
+    static constexpr int RBLKS = ROWS / MB;                         // blocks of MB rows
+    static constexpr int BLOCKS = RBLKS * 8, CHUNKS = ROWS * 8;     // MB x KCH blocks / 16-byte chunks per tile
+    static constexpr int IT = K_CONTIGUOUS ? (CHUNKS + NT - 1) / NT : (BLOCKS + NT - 1) / NT;
+    int raw[IT][K_CONTIGUOUS ? 1 : KCH][K_CONTIGUOUS ? 4 : AW];
+
+    static __device__ __forceinline__ uint32_t bits_of(const elt *src, int i)
+    {
+        if constexpr (ES == 4) return __builtin_bit_cast(uint32_t, src[i]);
+        else if constexpr (ES == 2) return (uint16_t)src[i];
+        else return (uint8_t)src[i];
+    }
+
+    // global -> registers for the K step that starts at k0; `r0` is the first row of the tile, `nrows`
+    // and `K` bound the operand; `inside`: every row of the tile exists and the step is a full one
+    __device__ __forceinline__ void load(const elt *__restrict__ src, int64_t ld, int r0, int k0, int nrows, int K,
+                                         bool inside, int tid)
+    {
+        if constexpr (K_CONTIGUOUS) {
+            // 16-byte chunks along k; 8 consecutive lanes cover one 128-byte row segment
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int cid = tid + it * NT;
+                if (CHUNKS % NT != 0 && cid >= CHUNKS) continue;
+                const int row = cid >> 3, ch = cid & 7;
+                const int r = r0 + row, k = k0 + ch * KCH;
+                const elt *q = src + (int64_t)r * ld + k;
+                v4i v;
+                if (inside || (r < nrows && k + KCH <= K)) {
+                    v = *(const v4i_u *)q;                          // the whole chunk exists: one load at any alignment
+                } else {
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        uint32_t word = 0;
+#pragma unroll
+                        for (int e = 0; e < 4 / ES; ++e) {
+                            const int ki = w * (4 / ES) + e;
+                            const uint32_t bits = (r < nrows && k + ki < K) ? bits_of(q, ki) : 0u;
+                            word |= bits << (8 * ES * e);
+                        }
+                        v[w] = (int)word;
+                    }
+                }
+                raw[it][0][0] = v[0]; raw[it][0][1] = v[1]; raw[it][0][2] = v[2]; raw[it][0][3] = v[3];
+            }
+        } else {
+            // blocks of MB rows x KCH k; consecutive lanes take consecutive rows
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int bid = tid + it * NT;
+                if (BLOCKS % NT != 0 && bid >= BLOCKS) continue;
+                const int rblk = bid % RBLKS, kch = bid / RBLKS;
+                const int rb = r0 + rblk * MB;
+#pragma unroll
+                for (int kk = 0; kk < KCH; ++kk) {
+                    const int k = k0 + kch * KCH + kk;
+                    const elt *q = src + (int64_t)k * ld + rb;
+                    if (inside || (k < K && rb + MB <= nrows)) {
+                        if constexpr (AW == 4) {
+                            const v4i v = *(const v4i_u *)q;
+                            raw[it][kk][0] = v[0]; raw[it][kk][1] = v[1]; raw[it][kk][2] = v[2]; raw[it][kk][3] = v[3];
+                        } else if constexpr (AW == 2) {
+                            const v2i v = *(const v2i_u *)q;
+                            raw[it][kk][0] = v[0]; raw[it][kk][1] = v[1];
+                        } else {
+                            raw[it][kk][0] = *(const i32_u *)q;
+                        }
+                        continue;
+                    }
+#pragma unroll
+                    for (int w = 0; w < AW; ++w) {
+                        uint32_t word = 0;
+#pragma unroll
+                        for (int e = 0; e < 4 / ES; ++e) {
+                            const int ri = w * (4 / ES) + e;
+                            const uint32_t bits = (k < K && rb + ri < nrows) ? bits_of(q, ri) : 0u;
+                            word |= bits << (8 * ES * e);
+                        }
+                        raw[it][kk][w] = (int)word;
+                    }
+                }
+            }
+        }
+    }
+
+    // registers -> LDS rows of this operand (`rows` points at its first tile row in a buffer)
+    __device__ __forceinline__ void store(unsigned char *rows, int tid)
+    {
+        if constexpr (K_CONTIGUOUS) {
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int cid = tid + it * NT;
+                if (CHUNKS % NT != 0 && cid >= CHUNKS) continue;
+                const int row = cid >> 3, ch = cid & 7;
+                v4i v = {raw[it][0][0], raw[it][0][1], raw[it][0][2], raw[it][0][3]};
+                *(v4i *)(rows + row * ROWB + ch * 16) = v;
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int bid = tid + it * NT;
+                if (BLOCKS % NT != 0 && bid >= BLOCKS) continue;
+                const int rblk = bid % RBLKS, kch = bid / RBLKS;
+                unsigned char *dst = rows + (rblk * MB) * ROWB + kch * 16;
+                if constexpr (ES == 1) {
+                    v4i out[MB];
+                    Transpose<DT, MB>::all(raw[it], out);
+#pragma unroll
+                    for (int c = 0; c < MB; ++c) *(v4i *)(dst + c * ROWB) = out[c];
+                } else {
+#pragma unroll
+                    for (int c = 0; c < MB; ++c) *(v4i *)(dst + c * ROWB) = Transpose<DT, MB>::chunk(raw[it], c);
+                }
+            }
+        }
+    }
+};
+
+// A_KC: A has K contiguous (a transposed A of a column-major problem); B_NC: B has N contiguous (a
+// transposed B).  The canonical problem is <false, false>.
+template <class T, bool A_KC = false, bool B_NC = false>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 {
     typedef typename T::DT DT;
     typedef typename DT::elt elt;
-    typedef typename DT::acc_t acc_t;
     typedef typename DT::accv accv;
-    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, ROWB = T::ROWB;
-    constexpr int TM = T::TM, TN = T::TN, MB = T::MB, KCH = DT::KCH, ES = DT::ES;
-    constexpr int A_IT = T::A_IT, B_IT = T::B_IT, AW = T::AW;
-    constexpr int MBLKS = BM / MB;                   // A blocks along m
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, ROWB = T::ROWB;
+    constexpr int TM = T::TM, TN = T::TN;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -307,8 +432,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
     const elt *__restrict__ A = (const elt *)p.A;
     const elt *__restrict__ B = (const elt *)p.B;
     // interior tiles take whole-vector loads whatever the alignment of the operands
-    const bool tile_vec_a = (m0 + BM <= p.M);
-    const bool tile_vec_b = (n0 + BN <= p.N);
+    const bool tile_in_a = (m0 + BM <= p.M);
+    const bool tile_in_b = (n0 + BN <= p.N);
 
     accv acc[TM][TN];
 #pragma unroll
@@ -318,146 +443,21 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    int rawA[A_IT][KCH][AW];
-    v4i rawB[B_IT];
+    StagedOperand<T, BM, A_KC> opa;
+    StagedOperand<T, BN, !B_NC> opb;
 
     // ---- global -> registers for K step kt
     auto load_tiles = [&](int kt) {
         const int k0 = kt * BK;
         const bool kfull = (k0 + BK <= p.K);
-        // A: blocks of MB (m) x KCH (k); consecutive lanes take consecutive m
-        if (tile_vec_a && kfull) {
-#pragma unroll
-            for (int it = 0; it < A_IT; ++it) {
-                const int bid = tid + it * NT;
-                if (T::A_BLOCKS % NT != 0 && bid >= T::A_BLOCKS) continue;
-                const int mblk = bid % MBLKS, kch = bid / MBLKS;
-                const elt *src = A + (int64_t)(k0 + kch * KCH) * p.lda + (m0 + mblk * MB);
-#pragma unroll
-                for (int kk = 0; kk < KCH; ++kk) {
-                    if constexpr (AW == 4) {
-                        v4i v = *(const v4i_u *)(src + (int64_t)kk * p.lda);
-                        rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1]; rawA[it][kk][2] = v[2]; rawA[it][kk][3] = v[3];
-                    } else if constexpr (AW == 2) {
-                        v2i v = *(const v2i_u *)(src + (int64_t)kk * p.lda);
-                        rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1];
-                    } else {
-                        rawA[it][kk][0] = *(const i32_u *)(src + (int64_t)kk * p.lda);
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < A_IT; ++it) {
-                const int bid = tid + it * NT;
-                if (T::A_BLOCKS % NT != 0 && bid >= T::A_BLOCKS) continue;
-                const int mblk = bid % MBLKS, kch = bid / MBLKS;
-                const int mb = m0 + mblk * MB;
-#pragma unroll
-                for (int kk = 0; kk < KCH; ++kk) {
-                    const int k = k0 + kch * KCH + kk;
-                    const elt *src = A + (int64_t)k * p.lda + mb;
-                    if (k < p.K && mb + MB <= p.M) {
-                        // the whole vector exists: one load, whatever its alignment
-                        if constexpr (AW == 4) {
-                            const v4i v = *(const v4i_u *)src;
-                            rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1]; rawA[it][kk][2] = v[2]; rawA[it][kk][3] = v[3];
-                        } else if constexpr (AW == 2) {
-                            const v2i v = *(const v2i_u *)src;
-                            rawA[it][kk][0] = v[0]; rawA[it][kk][1] = v[1];
-                        } else {
-                            rawA[it][kk][0] = *(const i32_u *)src;
-                        }
-                        continue;
-                    }
-#pragma unroll
-                    for (int w = 0; w < AW; ++w) {
-                        uint32_t word = 0;
-#pragma unroll
-                        for (int e = 0; e < 4 / ES; ++e) {
-                            const int mi = w * (4 / ES) + e;
-                            uint32_t bits = 0;
-                            if (k < p.K && mb + mi < p.M) {
-                                if constexpr (ES == 4) bits = __builtin_bit_cast(uint32_t, src[mi]);
-                                else if constexpr (ES == 2) bits = (uint16_t)src[mi];
-                                else bits = (uint8_t)src[mi];
-                            }
-                            word |= bits << (8 * ES * e);
-                        }
-                        rawA[it][kk][w] = (int)word;
-                    }
-                }
-            }
-        }
-        // B: 16-byte chunks along k; 8 consecutive lanes cover one 128-byte row segment
-        if (tile_vec_b && kfull) {
-#pragma unroll
-            for (int it = 0; it < B_IT; ++it) {
-                const int cid = tid + it * NT;
-                if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
-                const int row = cid >> 3, ch = cid & 7;
-                rawB[it] = *(const v4i_u *)(B + (int64_t)(n0 + row) * p.ldb + (k0 + ch * KCH));
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < B_IT; ++it) {
-                const int cid = tid + it * NT;
-                if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
-                const int row = cid >> 3, ch = cid & 7;
-                const int n = n0 + row;
-                const elt *src = B + (int64_t)n * p.ldb + (k0 + ch * KCH);
-                v4i v;
-                if (n < p.N && k0 + ch * KCH + KCH <= p.K) {
-                    rawB[it] = *(const v4i_u *)src;      // the whole chunk exists: one load at any alignment
-                    continue;
-                }
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    uint32_t word = 0;
-#pragma unroll
-                    for (int e = 0; e < 4 / ES; ++e) {
-                        const int ki = w * (4 / ES) + e;
-                        uint32_t bits = 0;
-                        if (n < p.N && k0 + ch * KCH + ki < p.K) {
-                            if constexpr (ES == 4) bits = __builtin_bit_cast(uint32_t, src[ki]);
-                            else if constexpr (ES == 2) bits = (uint16_t)src[ki];
-                            else bits = (uint8_t)src[ki];
-                        }
-                        word |= bits << (8 * ES * e);
-                    }
-                    v[w] = (int)word;
-                }
-                rawB[it] = v;
-            }
-        }
+        opa.load(A, p.lda, m0, k0, p.M, p.K, tile_in_a && kfull, tid);
+        opb.load(B, p.ldb, n0, k0, p.N, p.K, tile_in_b && kfull, tid);
     };
-
     // ---- registers -> LDS buffer `buf` (the packing step): rows of 128 bytes, K contiguous
     auto store_tiles = [&](int buf) {
         unsigned char *base = smem + buf * T::STAGE;
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-            const int bid = tid + it * NT;
-            if (T::A_BLOCKS % NT != 0 && bid >= T::A_BLOCKS) continue;
-            const int mblk = bid % MBLKS, kch = bid / MBLKS;
-            unsigned char *dst = base + (mblk * MB) * ROWB + kch * 16;
-            if constexpr (ES == 1) {
-                v4i out[MB];
-                Transpose<DT, MB>::all(rawA[it], out);
-#pragma unroll
-                for (int c = 0; c < MB; ++c) *(v4i *)(dst + c * ROWB) = out[c];
-            } else {
-#pragma unroll
-                for (int c = 0; c < MB; ++c) *(v4i *)(dst + c * ROWB) = Transpose<DT, MB>::chunk(rawA[it], c);
-            }
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) {
-            const int cid = tid + it * NT;
-            if (T::B_CHUNKS % NT != 0 && cid >= T::B_CHUNKS) continue;
-            const int row = cid >> 3, ch = cid & 7;
-            *(v4i *)(base + (BM + row) * ROWB + ch * 16) = rawB[it];
-        }
+        opa.store(base, tid);
+        opb.store(base + BM * ROWB, tid);
     };
 
     // ---- the micro-kernel on one LDS buffer

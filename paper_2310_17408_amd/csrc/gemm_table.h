@@ -21,6 +21,7 @@ struct Params {
     uint32_t alpha_bits, beta_bits;
     int use_beta;          // beta != 0: the old C is read
     int vecA, vecB;        // operand rows are 16-byte aligned (direct global -> LDS transfers of 16 bytes)
+    int a_kc, b_nc;        // transposed operands: A has K contiguous / B has N contiguous (staged kernels only)
     int group_m;           // tiles per column group in the tile order
     int xcd_remap;         // deal contiguous tile ranges to the 8 XCDs
 };
@@ -53,6 +54,7 @@ struct KernelInfo {
     // fp16/int8 kernels then load through misaligned vectors, which the memory system splits, and the
     // direct ones stage every tile through registers.
     int unaligned_pct;
+    int transposed_ok;       // takes A with K contiguous and B with N contiguous as well (Params::a_kc, b_nc)
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8, 3 bf16

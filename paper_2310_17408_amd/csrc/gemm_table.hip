@@ -39,22 +39,30 @@ static hipError_t solo_dma32(int wg, int ks, int fill, hipStream_t st)
     return launch_solo<T>(&solo_kernel_direct<T, Dma32Micro<T>>, wg, ks, fill, st);
 }
 
-template <class T>
-static hipError_t launch_tile(const Params &p, hipStream_t stream)
+template <class T, bool A_KC, bool B_NC>
+static hipError_t launch_tile_variant(const Params &p, hipStream_t stream)
 {
     static bool attr_done[64] = {false};          // per device: allow LDS beyond the default limit
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !attr_done[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<T>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<T, A_KC, B_NC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done[dev] = true;
     }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
-    hipLaunchKernelGGL(gemm_kernel<T>, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_NC>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
     return hipGetLastError();
+}
+
+// the staged kernel in the orientation the problem has
+template <class T>
+static hipError_t launch_tile(const Params &p, hipStream_t stream)
+{
+    if (p.a_kc) return p.b_nc ? launch_tile_variant<T, true, true>(p, stream) : launch_tile_variant<T, true, false>(p, stream);
+    return p.b_nc ? launch_tile_variant<T, false, true>(p, stream) : launch_tile_variant<T, false, false>(p, stream);
 }
 
 template <class T>
@@ -133,7 +141,7 @@ template <class T>
 static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, setup_ns,
-                      &solo_staged<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, T::DT::ES == 4 ? 0 : 30};
+                      &solo_staged<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, T::DT::ES == 4 ? 0 : 30, 1};
 }
 
 // Staged kernels:  dtype BM   BN  waves  MB  min workgroups per CU

@@ -1,0 +1,110 @@
+"""GPU parity of the general entry point gemm_ex (transposed operands, every data type) against the
+oracle's gemm_ex, element by element, on seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2310_17408_amd as mg
+from gpu_case import DT, LAYOUT, TOL, max_abs, to_device
+
+pytestmark = pytest.mark.gpu
+
+GEN = {"f32": wl.uniform_f32, "f16": wl.normal_f16_bits, "bf16": wl.normal_bf16_bits, "i8": wl.uniform_i8}
+SMALL = {"f32": wl.small_int_f32, "f16": wl.small_int_f16_bits, "bf16": wl.small_int_bf16_bits}
+
+
+def _case(dtype, layout, ta, tb, M, N, K, alpha, beta, seed, pad=(0, 0, 0), kernel_id=-1, split=0, exact=False):
+    ar, ac = (K, M) if ta else (M, K)          # the stored matrices
+    br, bc = (N, K) if tb else (K, N)
+    lda = wl.tight_ld(layout, ar, ac) + pad[0]
+    ldb = wl.tight_ld(layout, br, bc) + pad[1]
+    ldc = wl.tight_ld(layout, M, N) + pad[2]
+    gen = SMALL[dtype] if exact else GEN[dtype]
+    A, B = gen(seed, layout, ar, ac, lda), gen(seed + 1, layout, br, bc, ldb)
+    if dtype == "i8":
+        C = wl.uniform_i32(seed + 2, layout, M, N, ldc)
+    else:
+        C = (wl.small_int_f32 if exact else wl.uniform_f32)(seed + 2, layout, M, N, ldc)
+    _, dA = to_device(A)
+    _, dB = to_device(B)
+    _, dC = to_device(C)
+    nbytes = max(mg.gemm_workspace_bytes(DT[dtype], M, N, K), max(split, 1) * M * N * 4, 16)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    mg.gemm_force_kernel(DT[dtype], kernel_id, split)
+    try:
+        mg.gemm_ex(DT[dtype], LAYOUT[layout], ta, tb, M, N, K, alpha, dA, lda, dB, ldb, beta, dC, ldc, ws)
+        kid, ks = mg.gemm_last_kernel_id(), mg.gemm_last_split()
+    finally:
+        mg.gemm_force_kernel(DT[dtype], -1, 0)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy().reshape(C.shape)
+    ref = oracle.gemm_ex(dtype, layout, ta, tb, M, N, K, alpha, A, lda, B, ldb, beta, C if beta != 0 else None, ldc)
+    got = wl.logical(layout, out, M, N)
+    what = "%s %s ta=%d tb=%d %dx%dx%d kernel %s split %d" % (dtype, layout, ta, tb, M, N, K,
+                                                            mg.gemm_kernel_name(DT[dtype], kid), ks)
+    if dtype == "i8":
+        assert np.array_equal(got, oracle.wrap_int32(ref)), what
+    elif exact:
+        assert np.array_equal(got.astype(np.float64), ref), what
+    else:
+        err = oracle.normalised_error(got, ref, K, max_abs(dtype, layout, A, ar, ac) or 1.0,
+                                      max_abs(dtype, layout, B, br, bc) or 1.0)
+        assert err <= TOL[dtype], "%s: normalised error %.3e" % (what, err)
+    mask = np.ones(out.shape, dtype=bool)
+    wl.logical(layout, mask, M, N)[...] = False
+    assert np.array_equal(out[mask], np.asarray(C)[mask]), what + ": padding of C was overwritten"
+    return kid, ks
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8"])
+@pytest.mark.parametrize("layout", ["col", "row"])
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1), (1, 1)])
+def test_gemm_ex_all_orientations(dtype, layout, ta, tb):
+    a, b = (3, -2) if dtype == "i8" else (1.5, 0.5)
+    # several tiles of every staged configuration, 16-byte aligned rows
+    _case(dtype, layout, ta, tb, 320, 272, 192, a, b, seed=7000)
+    # ragged everywhere, odd leading dimensions, a K tail
+    _case(dtype, layout, ta, tb, 133, 77, 91, a, b, seed=7100, pad=(1, 2, 3))
+    # tiny
+    _case(dtype, layout, ta, tb, 7, 5, 3, 1, 0, seed=7200)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8"])
+@pytest.mark.parametrize("ta,tb", [(1, 0), (0, 1), (1, 1)])
+def test_gemm_ex_transposed_every_staged_kernel_and_split(dtype, ta, tb):
+    """Every configuration that takes transposed operands, unsplit and with K split over workgroups;
+    a forced configuration that does not take them must be replaced, not run."""
+    n = mg.gemm_kernel_count(DT[dtype])
+    ran = set()
+    for kid in range(n):
+        a, b = (1, 1) if dtype == "i8" else (1.0, 1.0)
+        k, s = _case(dtype, "col", ta, tb, 200, 136, 700, a, b, seed=7300 + kid, kernel_id=kid)
+        ran.add(k)
+        k2, s2 = _case(dtype, "row", ta, tb, 200, 136, 2100, a, b, seed=7400 + kid, kernel_id=kid, split=3)
+        assert s2 == 3 or k2 != kid
+    assert len(ran) >= 2          # at least the 64x64 and one larger staged tile ran
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("ta,tb", [(1, 0), (0, 1), (1, 1)])
+def test_gemm_ex_small_integers_exact(dtype, ta, tb):
+    for layout in ("col", "row"):
+        _case(dtype, layout, ta, tb, 150, 140, 1024, 2, -1, seed=7500, exact=True)
+
+
+def test_gemm_ex_untransposed_is_the_plain_entry_point():
+    """transa = transb = 0 selects and computes exactly what gemm_f32 does."""
+    M, N, K = 300, 200, 150
+    A, B, C = wl.uniform_f32(1, "col", M, K), wl.uniform_f32(2, "col", K, N), wl.uniform_f32(3, "col", M, N)
+    _, dA = to_device(A)
+    _, dB = to_device(B)
+    _, c1 = to_device(C)
+    _, c2 = to_device(C)
+    mg.gemm_f32(mg.COL_MAJOR, M, N, K, 1.5, dA, M, dB, K, 0.5, c1, M)
+    k1 = mg.gemm_last_kernel_id()
+    mg.gemm_ex(mg.F32, mg.COL_MAJOR, 0, 0, M, N, K, 1.5, dA, M, dB, K, 0.5, c2, M)
+    assert mg.gemm_last_kernel_id() == k1
+    torch.cuda.synchronize()
+    assert torch.equal(c1, c2)

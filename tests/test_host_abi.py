@@ -128,3 +128,32 @@ def test_timing_model_and_selection_agree():
         mg.gemm_predict_us(mg.F32, 99, 10, 10, 10, 1)
     with pytest.raises(mg.GemmError):
         mg.gemm_predict_us(mg.F32, 0, 10, 10, 10, 0)
+
+
+def test_gemm_ex_argument_errors():
+    """Status -k names the k-th argument of gemm_ex's own list; nothing is launched."""
+    P = 0x1000
+    ok = dict(dtype=mg.F32, layout=0, ta=0, tb=0, M=8, N=6, K=4, lda=8, ldb=4, ldc=8)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return mg.gemm_ex(a["dtype"], a["layout"], a["ta"], a["tb"], a["M"], a["N"], a["K"], 1.0, P, a["lda"], P, a["ldb"],
+                          0.0, P, a["ldc"], None, check=False)
+
+    assert call(dtype=9) == -1
+    assert call(layout=2) == -2
+    assert call(ta=2) == -3
+    assert call(tb=-1) == -4
+    assert call(M=-1) == -5 and call(N=-1) == -6 and call(K=-1) == -7
+    # leading dimensions follow the stored matrix: a transposed A is K x M
+    assert call(lda=7) == -10 and call(ta=1, lda=3) == -10 and call(ta=1, lda=4, M=0) == 0
+    assert call(ldb=3) == -12 and call(tb=1, ldb=5) == -12
+    assert call(layout=1, lda=3) == -10 and call(layout=1, ta=1, lda=7) == -10
+    assert call(ldc=7) == -15
+    assert "argument 10 (lda)" in mg.load().gemm_ex_status_string(-10).decode()
+    assert "transa" in mg.load().gemm_ex_status_string(-3).decode()
+    lib = mg.load()
+    import ctypes
+    one = ctypes.c_float(1.0)
+    assert lib.gemm_ex(0, 0, 0, 0, 8, 6, 4, None, P, 8, P, 4, ctypes.byref(one), P, 8, None, 0, None) == -8
+    assert lib.gemm_ex(0, 0, 0, 0, 8, 6, 4, ctypes.byref(one), P, 8, P, 4, None, P, 8, None, 0, None) == -13

@@ -419,3 +419,52 @@ def test_bf16_small_integers_match_fp32_oracle(layout):
     D = oracle.gemm_f32(layout, M, N, K, 2.0, A, lda, B, ldb, -1.0, C, ldc)
     Db = oracle.gemm_bf16(layout, M, N, K, 2.0, wl._to_bf16_bits(A), lda, wl._to_bf16_bits(B), ldb, -1.0, C, ldc)
     assert np.array_equal(Db, D)
+
+
+# ---------------------------------------------------------------- transposed operands
+def _stored(layout, logical_matrix, ld_pad):
+    """Buffer holding `logical_matrix` (rows x cols) in `layout` with a padded leading dimension."""
+    rows, cols = logical_matrix.shape
+    ld = wl.tight_ld(layout, rows, cols) + ld_pad
+    buf = np.zeros(wl._shape(layout, rows, cols, ld), dtype=logical_matrix.dtype)
+    wl.logical(layout, buf, rows, cols)[...] = logical_matrix
+    return buf, ld
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1), (1, 1)])
+def test_transposed_operands_exact_rational_and_against_plain(layout, ta, tb):
+    """op(A) = A^T / op(B) = B^T: exact rational brute force on 7x5x3 from the stored matrices, and
+    identity with the plain oracle on explicitly transposed copies (every data type)."""
+    M, N, K = 7, 5, 3
+    rng = np.random.default_rng(900 + 2 * ta + tb)
+    opA = (rng.random((M, K), dtype=np.float32) * 2 - 1).astype(np.float32)
+    opB = (rng.random((K, N), dtype=np.float32) * 2 - 1).astype(np.float32)
+    Cm = (rng.random((M, N), dtype=np.float32) * 2 - 1).astype(np.float32)
+    A, lda = _stored(layout, opA.T.copy() if ta else opA, 2)
+    B, ldb = _stored(layout, opB.T.copy() if tb else opB, 1)
+    C, ldc = _stored(layout, Cm, 3)
+    D = oracle.gemm_ex("f32", layout, ta, tb, M, N, K, 1.5, A, lda, B, ldb, 0.5, C, ldc)
+    for i in range(M):
+        for j in range(N):
+            s = sum(Fraction(float(opA[i, p])) * Fraction(float(opB[p, j])) for p in range(K))
+            want = Fraction(3, 2) * s + Fraction(1, 2) * Fraction(float(Cm[i, j]))
+            assert abs(Fraction(float(D[i, j])) - want) <= Fraction(1, 2 ** 50)
+    # the plain oracle on untransposed copies computes the same sums in the same order
+    A0, lda0 = _stored(layout, opA, 0)
+    B0, ldb0 = _stored(layout, opB, 0)
+    assert np.array_equal(D, oracle.gemm_f32(layout, M, N, K, np.float32(1.5), A0, lda0, B0, ldb0, np.float32(0.5), C, ldc))
+    # 16-bit and 8-bit inputs
+    M, N, K = 33, 17, 40
+    for dtype, gen, plain in (("f16", wl.normal_f16_bits, oracle.gemm_f16), ("bf16", wl.normal_bf16_bits, oracle.gemm_bf16),
+                              ("i8", wl.uniform_i8, oracle.gemm_i8)):
+        opA = wl.logical("row", gen(910, "row", M, K), M, K)
+        opB = wl.logical("row", gen(911, "row", K, N), K, N)
+        A, lda = _stored(layout, opA.T.copy() if ta else opA.copy(), 1)
+        B, ldb = _stored(layout, opB.T.copy() if tb else opB.copy(), 2)
+        A0, lda0 = _stored(layout, opA.copy(), 0)
+        B0, ldb0 = _stored(layout, opB.copy(), 0)
+        one = 1 if dtype == "i8" else np.float32(1)
+        zero = 0 if dtype == "i8" else np.float32(0)
+        got = oracle.gemm_ex(dtype, layout, ta, tb, M, N, K, 1, A, lda, B, ldb, 0, None, 0)
+        assert np.array_equal(got, plain(layout, M, N, K, one, A0, lda0, B0, ldb0, zero, None, 0))
