@@ -82,8 +82,9 @@ def main():
     class Case:
         """One GEMM with its operands on the device."""
 
-        def __init__(self, dtype, layout, M, N, K, alpha, beta, seed):
+        def __init__(self, dtype, layout, M, N, K, alpha, beta, seed, trans=(0, 0)):
             self.dtype, self.layout, self.M, self.N, self.K = dtype, layout, M, N, K
+            self.trans = trans          # square problems only: the stored shapes do not change
             self.lda, self.ldb, self.ldc = wl.tight_ld(layout, M, K), wl.tight_ld(layout, K, N), wl.tight_ld(layout, M, N)
             if dtype == "f32":
                 A, B = wl.uniform_f32(seed, layout, M, K), wl.uniform_f32(seed + 1, layout, K, N)
@@ -105,6 +106,10 @@ def main():
             self.flop = 2.0 * M * N * K
 
         def run(self, on=stream):
+            if self.trans != (0, 0):
+                mg.gemm_ex(code[self.dtype], lay[self.layout], self.trans[0], self.trans[1], self.M, self.N, self.K,
+                           self.alpha, self.A, self.lda, self.B, self.ldb, self.beta, self.C, self.ldc, self.ws, on)
+                return
             fn[self.dtype](lay[self.layout], self.M, self.N, self.K, self.alpha, self.A, self.lda, self.B, self.ldb,
                            self.beta, self.C, self.ldc, self.ws, on)
 
@@ -231,6 +236,8 @@ def main():
             best = min(timed([case], reps) / reps for _ in range(3))
             row = {"config": label, "dtype": case.dtype, "layout": case.layout, "M": case.M, "N": case.N,
                    "K": case.K, "kernel": name, "split": split}
+            if case.trans != (0, 0):
+                row["transa"], row["transb"] = case.trans
             if best < 0.1:
                 # short GEMMs: back-to-back eager launches are bounded by the host's launch rate, so the
                 # figure of merit is the replay of a captured graph; the eager figure is kept beside it
@@ -253,6 +260,12 @@ def main():
         for i, n in enumerate(wl.FP16_SQUARES[1:]):
             measure("bf16 square (beyond the configurations)", Case("bf16", "row", n, n, n, 1.0, 0.0, 3500 + i))
             torch.cuda.empty_cache()
+        for trans in ((1, 0), (0, 1), (1, 1)):
+            measure("transposed operands (beyond the configurations)",
+                    Case("f32", "col", 4096, 4096, 4096, 1.0, 0.0, 3600, trans=trans))
+        measure("transposed operands (beyond the configurations)",
+                Case("f16", "col", 4096, 4096, 4096, 1.0, 0.0, 3601, trans=(1, 0)))
+        torch.cuda.empty_cache()
         for i, (M, N, K) in enumerate(wl.IM2ROW_HEADLINE):
             for layout in ("col", "row"):
                 measure("c4 im2row", Case("f32", layout, M, N, K, 1.0, 0.0, 4000 + i), cold=True)
