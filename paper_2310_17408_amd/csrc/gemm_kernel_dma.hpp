@@ -123,9 +123,10 @@ struct DmaMicro {
     typedef typename T::DT DT;
     typedef typename DT::accv accv;
     static constexpr int TM = T::TM, TN = T::TN, ES = T::ES, KCH = T::KCH, A_ROWB = T::A_ROWB, KH = T::KH;
-    // the fragments of one step: per block row / column 16 bytes = KCH consecutive k
-    struct aset { v4i v[TM]; };
-    struct bset { v4i v[TN]; };
+    static constexpr int STEPS = T::KSTEPS;          // fragment steps per stage (an even number)
+    static constexpr int ACC = 16;
+    // the fragments of one step, double buffered: per block row / column 16 bytes = KCH consecutive k
+    v4i fa[2][TM], fb[2][TN];
     uint32_t aoff[TM], boff[T::KSTEPS];
 
     // fragment addresses of this lane inside a stage, for the wave whose tile starts at (wm0, wn0)
@@ -150,45 +151,176 @@ struct DmaMicro {
         }
     }
 
-    // LDS reads of fragment step s (2*KCH consecutive k) of the stage at `stage`
-    __device__ __forceinline__ void load(const unsigned char *stage, int s, aset &xa, bset &xb) const
+    // two transposing reads give a lane KCH consecutive k of its m
+    static __device__ __forceinline__ v4i read_a(const unsigned char *q0)
     {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            // two transposing reads give this lane KCH consecutive k of its m
-            const unsigned char *q0 = stage + aoff[i] + (2 * KCH * s) * A_ROWB;
-            const unsigned char *q1 = q0 + KH * A_ROWB;
-            if constexpr (ES == 2) {
-                v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
-                v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
-                xa.v[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
-            } else {
-                v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
-                v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
-                xa.v[i] = v4i{lo[0], lo[1], hi[0], hi[1]};
-            }
+        const unsigned char *q1 = q0 + KH * A_ROWB;
+        if constexpr (ES == 2) {
+            v2i lo = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q0));
+            v2i hi = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MIG_LDS v4s *)q1));
+            return v4i{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+            v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q0);
+            v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MIG_LDS v2i *)q1);
+            return v4i{lo[0], lo[1], hi[0], hi[1]};
         }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) xb.v[j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
     }
 
-    static __device__ __forceinline__ void mma(aset &xa, bset &xb, accv (&acc)[TM][TN])
+    // LDS reads of fragment step s (2*KCH consecutive k) of the stage at `stage` into set s%2
+    __device__ __forceinline__ void load(const unsigned char *stage, int s)
+    {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[s & 1][i] = read_a(stage + aoff[i] + (2 * KCH * s) * A_ROWB);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[s & 1][j] = *(const v4i *)(stage + boff[s] + j * 32 * T::B_ROWB);
+    }
+
+    // the MFMAs of fragment step s
+    __device__ __forceinline__ void mma(int s, accv (&acc)[TM][TN])
     {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) Mma<DT>::run(xb.v[j], xa.v[i], acc[i][j]);
+            for (int j = 0; j < TN; ++j) Mma<DT>::run(fb[s & 1][j], fa[s & 1][i], acc[i][j]);
+    }
+
+    static __device__ __forceinline__ void store(accv (&acc)[TM][TN], const Params &p, int m0, int n0, int wm0, int wn0,
+                                                 int lane, int z, int m_own, int n_own)
+    {
+        store_tile<DT, TM, TN>(acc, p, m0, n0, T::BM, T::BN, wm0, wn0, lane, z, m_own, n_own);
+    }
+};
+
+// The same wave tile cut into 16 x 16 blocks for the MFMA shapes with the deepest K per
+// instruction (16x16x32 for 16-bit inputs, 16x16x64 for int8).  They update a quarter of the
+// accumulators per multiply-add of the 32 x 32 shapes; on random operands the chip, which lowers
+// its clock under the power these instructions draw, sustains 18-25 % more with them (register-only
+// loops: fp16 1.83 against 1.55 PFLOP/s, bf16 2.02 against 1.71, int8 4.13 against 3.31 POP/s).
+// A lane holds row (or column) lane%16 and the k group lane/16 of 4: KCH consecutive k per fragment.
+// A fragment step covers 4*KCH k; it is taken in two halves of the wave tile's rows so that the
+// fragments in flight stay at 16 + 16 registers per set: sub-step s = (k step s/2, row half s%2);
+// the B fragments are read with the first half and kept for the second.
+template <class DT> struct Mma16;
+template <> struct Mma16<F16> {
+    typedef v4f accv;
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v4f &c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, rowop), __builtin_bit_cast(v8h, colop), c, 0, 0, 0);
+    }
+};
+template <> struct Mma16<BF16> {
+    typedef v4f accv;
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v4f &c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, rowop), __builtin_bit_cast(v8bf, colop), c, 0, 0, 0);
+    }
+};
+template <> struct Mma16<I8> {
+    typedef v4i accv;
+    static __device__ __forceinline__ void run(const v4i &rowop, const v4i &colop, v4i &c) {
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(rowop, colop, c, 0, 0, 0);
     }
 };
 
 template <class T>
+struct DmaMicro16 {
+    typedef typename T::DT DT;
+    typedef typename Mma16<DT>::accv accv;
+    static constexpr int TM = T::WM / 16, TN = T::WN / 16, HM = TM / 2;
+    static constexpr int ES = T::ES, KCH = T::KCH, A_ROWB = T::A_ROWB, KH = T::KH;
+    static constexpr int STEPS = T::KSTEPS;          // sub-steps per stage: KSTEPS/2 k steps x 2 row halves
+    static constexpr int ACC = 4;
+    static_assert(T::KSTEPS % 2 == 0 && TM % 2 == 0, "k steps of 4 chunks, two row halves");
+    v4i fa[2][HM], fb[2][TN];
+    uint32_t aoff[TM], boff[T::KSTEPS / 2];
+
+    __device__ __forceinline__ void init(int lane, int wm0, int wn0)
+    {
+        const int r = lane & 15, g = lane >> 4;
+        // B: row wn0 + 16*j + r, logical chunk 4*ks + g; the swizzle of the row depends on r only
+        const int x = (r / T::B_RP256) % T::B_CPR;
+#pragma unroll
+        for (int ks = 0; ks < T::KSTEPS / 2; ++ks)
+            boff[ks] = T::A_BYTES + (wn0 + r) * T::B_ROWB + (((4 * ks + g) ^ x) << 4);
+        // A: the 16-lane group g reads k group g of the 16 rows of a block; inside it, lane r
+        // addresses k-row r/LPR and the (r%LPR)-th 8-byte piece of the 16 m
+        const int kr = r / T::LPR, ml = r % T::LPR;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mbyte = (wm0 + 16 * i) * ES + 8 * ml;
+            const int ch = (mbyte >> 4) ^ ((kr & T::SWZ_MASK) << T::SWZ_SHIFT);
+            aoff[i] = (KCH * g + kr) * A_ROWB + (ch << 4) + (mbyte & 15);
+        }
+    }
+
+    __device__ __forceinline__ void load(const unsigned char *stage, int s)
+    {
+        const int ks = s >> 1, mh = s & 1;
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
+            fa[s & 1][i] = DmaMicro<T>::read_a(stage + aoff[mh * HM + i] + (4 * KCH * ks) * A_ROWB);
+        if (mh == 0) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[ks & 1][j] = *(const v4i *)(stage + boff[ks] + j * 16 * T::B_ROWB);
+        }
+    }
+
+    __device__ __forceinline__ void mma(int s, accv (&acc)[TM][TN])
+    {
+        const int ks = s >> 1, mh = s & 1;
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) Mma16<DT>::run(fb[ks & 1][j], fa[s & 1][i], acc[mh * HM + i][j]);
+    }
+
+    // In a 16 x 16 block a lane holds row m = lane%16 and the columns n = 4*(lane/16) + v.
+    static __device__ __forceinline__ void store(accv (&acc)[TM][TN], const Params &p, int m0, int n0, int wm0, int wn0,
+                                                 int lane, int z, int m_own, int n_own)
+    {
+        typedef typename DT::acc_t acc_t;
+        const int r = lane & 15, g = lane >> 4;
+        const bool interior = (m0 + T::BM <= p.M) && (n0 + T::BN <= p.N) && m0 == m_own && n0 == n_own;
+        const acc_t alpha = __builtin_bit_cast(acc_t, p.alpha_bits);
+        const acc_t beta = __builtin_bit_cast(acc_t, p.beta_bits);
+        const bool use_beta = p.use_beta != 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm0 + 16 * i + r;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int n = n0 + wn0 + 16 * j + 4 * g + v;
+                    if (interior || (m >= m_own && m < p.M && n >= n_own && n < p.N)) {
+                        const acc_t a = acc[i][j][v];
+                        if (p.split > 1) {
+                            ((acc_t *)p.ws)[((int64_t)z * p.N + n) * p.M + m] = a;
+                        } else {
+                            acc_t *c = (acc_t *)p.C + (int64_t)n * p.ldc + m;
+                            if constexpr (DT::ES == 1) {
+                                uint32_t o = (uint32_t)alpha * (uint32_t)a;
+                                if (use_beta) o += (uint32_t)beta * (uint32_t)(*c);
+                                *c = (int)o;
+                            } else {
+                                float o = alpha * a;
+                                if (use_beta) o += beta * (*c);
+                                *c = o;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+};
+
+template <class T, class Micro = DmaMicro<T>>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p)
 {
     typedef typename T::DT DT;
     typedef typename DT::elt elt;
-    typedef typename DT::accv accv;
+    typedef typename Micro::accv accv;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NW = T::NW, ES = T::ES, KCH = T::KCH;
-    constexpr int TM = T::TM, TN = T::TN, A_CPR = T::A_CPR;
+    constexpr int TM = Micro::TM, TN = Micro::TN, A_CPR = T::A_CPR;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(MIG_LDS unsigned char *)smem;
@@ -293,7 +425,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
         stage_guarded(kt, buf, tile_fast_a && kfull, tile_fast_b && kfull);
     };
 
-    DmaMicro<T> micro;
+    Micro micro;
     micro.init(lane, wm0, wn0);
 
     accv acc[TM][TN];
@@ -302,29 +434,23 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+            for (int v = 0; v < Micro::ACC; ++v) acc[i][j][v] = 0;
 
-    // ---- the micro-kernel: KSTEPS fragment steps of 2*KCH consecutive k per stage.  Fragments are
-    // double buffered in registers: while the MFMAs of one step run, the LDS reads of the next are
-    // in flight, also across the barrier that ends a K step.
-    typename DmaMicro<T>::aset fa[2];
-    typename DmaMicro<T>::bset fb[2];
-    auto load_frags = [&](int buf, int s, typename DmaMicro<T>::aset &xa, typename DmaMicro<T>::bset &xb) {
-        micro.load(smem + buf * T::STAGE, s, xa, xb);
-    };
-    auto mma_step = [&](typename DmaMicro<T>::aset &xa, typename DmaMicro<T>::bset &xb) {
-        DmaMicro<T>::mma(xa, xb, acc);
-    };
-    // all but the last step of the stage `buf`; on entry the fragments of its step 0 are in set 0
+    // ---- the micro-kernel: Micro::STEPS fragment steps per stage.  Fragments are double buffered in
+    // registers (inside `micro`): while the MFMAs of one step run, the LDS reads of the next are in
+    // flight, also across the barrier that ends a K step.
+    auto load_frags = [&](int buf, int s) { micro.load(smem + buf * T::STAGE, s); };
+    auto mma_step = [&](int s) { micro.mma(s, acc); };
+    // all but the last step of the stage `buf`; on entry the fragments of its step 0 have been read
     auto steps_but_last = [&](int buf) {
 #pragma unroll
-        for (int s = 0; s + 1 < T::KSTEPS; ++s) {
-            load_frags(buf, s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
-            mma_step(fa[s & 1], fb[s & 1]);
+        for (int s = 0; s + 1 < Micro::STEPS; ++s) {
+            load_frags(buf, s + 1);
+            mma_step(s);
             __builtin_amdgcn_sched_barrier(0);   // keep each step's reads and MFMAs together
         }
     };
-    constexpr int LAST = (T::KSTEPS - 1) & 1;   // register set that holds the last step (KSTEPS is even)
+    constexpr int LAST = Micro::STEPS - 1;       // the last step of a stage
 
     // ---- K loop over NSTAGE LDS stages.  When the LDS reads of step i's last fragments have been
     // issued, the wave waits for its transfers of step i+1, meets the others at the barrier (now
@@ -345,7 +471,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
         wait_transfers<0>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        load_frags(0, 0, fa[0], fb[0]);
+        load_frags(0, 0);
         int buf = 0;
         int i = 0;
         for (; i + NS < nfast; ++i) {
@@ -357,9 +483,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             stage_dma(kt_begin + i + NS, buf);
-            load_frags(nxt, 0, fa[0], fb[0]);
+            load_frags(nxt, 0);
             __builtin_amdgcn_sched_barrier(0);
-            mma_step(fa[LAST], fb[LAST]);
+            mma_step(LAST);
             buf = nxt;
         }
         for (; i < nkt; ++i) {
@@ -370,15 +496,15 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
                 if (i + NS < nkt) stage_tiles(kt_begin + i + NS, buf);
-                load_frags(nxt, 0, fa[0], fb[0]);
+                load_frags(nxt, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            mma_step(fa[LAST], fb[LAST]);
+            mma_step(LAST);
             buf = nxt;
         }
     }
 
-    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z, m_own, n_own);
+    Micro::store(acc, p, m0, n0, wm0, wn0, lane, z, m_own, n_own);
 }
 
 }  // namespace mig

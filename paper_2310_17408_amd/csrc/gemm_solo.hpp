@@ -107,6 +107,36 @@ __global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_direct(int ksteps,
     solo_finish(acc);
 }
 
+// fp16 / bf16 / int8 direct kernels (gemm_kernel_dma.hpp): Micro is DmaMicro<T> or DmaMicro16<T>, which
+// hold their own double-buffered fragments
+template <class T, class Micro>
+__global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_micro(int ksteps, int fill)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    solo_fill<T::DT::ES, T::NT>(smem, T::STAGE, fill);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm0 = (wave % T::WAVES_M) * T::WM, wn0 = (wave / T::WAVES_M) * T::WN;
+    Micro micro;
+    micro.init(lane, wm0, wn0);
+    typename Micro::accv acc[Micro::TM][Micro::TN];
+#pragma unroll
+    for (int i = 0; i < Micro::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Micro::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < Micro::ACC; ++v) acc[i][j][v] = 0;
+    micro.load(smem, 0);
+    for (int it = 0; it < ksteps; ++it) {
+#pragma unroll
+        for (int s = 0; s < Micro::STEPS; ++s) {
+            micro.load(smem, (s + 1) % Micro::STEPS);
+            micro.mma(s, acc);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    solo_finish(acc);
+}
+
 // register-direct kernels (gemm_kernel_reg32.hpp): the operands of one K step stay in registers
 template <class T>
 __global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_reg(int ksteps, int fill)

@@ -28,10 +28,10 @@ static hipError_t launch_solo(K kernel, int workgroups, int ksteps, int fill, hi
 }
 template <class T>
 static hipError_t solo_staged(int wg, int ks, int fill, hipStream_t st) { return launch_solo<T>(&solo_kernel<T>, wg, ks, fill, st); }
-template <class T>
+template <class T, class Micro>
 static hipError_t solo_dma(int wg, int ks, int fill, hipStream_t st)
 {
-    return launch_solo<T>(&solo_kernel_direct<T, DmaMicro<T>>, wg, ks, fill, st);
+    return launch_solo<T>(&solo_kernel_micro<T, Micro>, wg, ks, fill, st);
 }
 template <class T>
 static hipError_t solo_dma32(int wg, int ks, int fill, hipStream_t st)
@@ -65,7 +65,7 @@ static hipError_t launch_tile(const Params &p, hipStream_t stream)
     return p.b_nc ? launch_tile_variant<T, false, true>(p, stream) : launch_tile_variant<T, false, false>(p, stream);
 }
 
-template <class T>
+template <class T, class Micro>
 static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
 {
     static bool attr_done[64] = {false};
@@ -73,21 +73,26 @@ static hipError_t launch_tile_dma(const Params &p, hipStream_t stream)
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !attr_done[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma<T>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma<T, Micro>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done[dev] = true;
     }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
-    hipLaunchKernelGGL(gemm_kernel_dma<T>, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((gemm_kernel_dma<T, Micro>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
-template <class T>
+template <class T, class Micro = DmaMicro<T>>
 static constexpr KernelInfo info_dma(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T>, prio, eff_pct, floor_ns, setup_ns,
-                      &solo_dma<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 30};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T, Micro>, prio, eff_pct, floor_ns,
+                      setup_ns, &solo_dma<T, Micro>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 30};
+}
+template <class T>
+static constexpr KernelInfo info_dma16(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
+{
+    return info_dma<T, DmaMicro16<T>>(name, prio, eff_pct, floor_ns, setup_ns);
 }
 
 template <class T>
@@ -183,22 +188,28 @@ static const KernelInfo k_f16[] = {
     info<F16_256x256>("f16_256x256_w128x128", 0, 50, 2500, 1500),
     info<F16_128x128>("f16_128x128_w64x64", 0, 47, 1700, 1500),
     info<F16_64x64>("f16_64x64_w32x32", 1, 40, 600, 1500),
-    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 1, 72, 880, 1500),
-    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 1, 82, 1800, 1500),
+    info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 0, 72, 880, 1500),
+    info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 0, 82, 1800, 1500),
+    info_dma16<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma16", 1, 87, 1700, 1500),
+    info_dma16<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma16", 1, 75, 850, 1500),
 };
 static const KernelInfo k_bf16[] = {
     info<BF16_256x256>("bf16_256x256_w128x128", 0, 50, 2500, 1500),
     info<BF16_128x128>("bf16_128x128_w64x64", 0, 47, 1700, 1500),
     info<BF16_64x64>("bf16_64x64_w32x32", 1, 40, 600, 1500),
-    info_dma<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma", 1, 72, 880, 1500),
-    info_dma<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma", 1, 82, 1800, 1500),
+    info_dma<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma", 0, 72, 880, 1500),
+    info_dma<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma", 0, 82, 1800, 1500),
+    info_dma16<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma16", 1, 87, 1700, 1500),
+    info_dma16<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma16", 1, 75, 850, 1500),
 };
 static const KernelInfo k_i8[] = {
     info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500, 1500),
     info<I8_128x128>("i8_128x128_w64x64", 0, 47, 800, 1500),
     info<I8_64x64>("i8_64x64_w32x32", 1, 30, 600, 1500),
-    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 1, 62, 880, 1500),
-    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 1, 75, 1800, 1500),
+    info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 0, 62, 880, 1500),
+    info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 0, 75, 1800, 1500),
+    info_dma16<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma16", 1, 80, 1700, 1500),
+    info_dma16<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma16", 1, 65, 850, 1500),
 };
 
 int kernel_count(int dtype)
