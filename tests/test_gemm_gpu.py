@@ -273,3 +273,42 @@ def test_solo_mode_runs_every_kernel(dtype):
     assert mg.gemm_solo(DT[dtype], 0, 0, 10, 1, check=False) == -3
     assert mg.gemm_solo(DT[dtype], 99, 8, 10, 1, check=False) == -2
     assert mg.gemm_solo(DT[dtype], 0, 8, 10, 2, check=False) == -5
+
+
+# ------------------------------------------------------------ leading dimensions beyond 32-bit byte offsets
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_huge_leading_dimension(dtype):
+    """lda of 2^26 + 8 elements: a k-row of A starts more than 2^28 bytes after the previous one, so the
+    kernels that address a tile with 32-bit lane offsets must step aside (selection) or take their
+    guarded path (when forced), and the result must still be right."""
+    M, N, K = 300, 40, 24
+    lda, ldb, ldc = (1 << 26) + 8, K, M
+    rng = np.random.default_rng(77)
+    if dtype == "f32":
+        A = np.zeros(K * lda, dtype=np.float32)
+        B = (rng.random(N * ldb, dtype=np.float32) * 2 - 1).astype(np.float32)
+        for k in range(K):
+            A[k * lda:k * lda + M] = rng.random(M, dtype=np.float32) * 2 - 1
+        ref_fn, amax = oracle.gemm_f32, 1.0
+    else:
+        A = np.zeros(K * lda, dtype=np.uint16)
+        B = wl.normal_f16_bits(78, "col", K, N).reshape(-1)
+        for k in range(K):
+            A[k * lda:k * lda + M] = wl.normal_f16_bits(79 + k, "col", M, 1).reshape(-1)
+        ref_fn, amax = oracle.gemm_f16, 6.0
+    C = np.zeros(N * ldc, dtype=np.float32)
+    ref = ref_fn("col", M, N, K, np.float32(1), A.reshape(K, lda), lda, B.reshape(N, ldb), ldb, np.float32(0), None, ldc)
+    kernels = [-1] + _kernels(dtype)
+    dA = torch.from_numpy(A.view(np.int16) if dtype == "f16" else A).cuda()
+    dB = torch.from_numpy(B.view(np.int16) if dtype == "f16" else B).cuda()
+    for kid in kernels:
+        dC = torch.from_numpy(C).cuda()
+        mg.gemm_force_kernel(DT[dtype], kid, 0)
+        try:
+            {"f32": mg.gemm_f32, "f16": mg.gemm_f16}[dtype](mg.COL_MAJOR, M, N, K, 1.0, dA, lda, dB, ldb, 0.0, dC, ldc)
+        finally:
+            mg.gemm_force_kernel(DT[dtype], -1, 0)
+        torch.cuda.synchronize()
+        got = dC.cpu().numpy().reshape(N, ldc)[:, :M].T
+        err = oracle.normalised_error(got, ref, K, amax, amax)
+        assert err <= (1e-6 if dtype == "f32" else 2e-3), (kid, err)
