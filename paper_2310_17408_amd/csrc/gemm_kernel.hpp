@@ -420,7 +420,11 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 
     int tm, tn;
     tile_coords(p, blockIdx.x, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    // a tile that sticks out of C is moved back to end at the edge (when the matrix has a whole tile of
+    // rows / columns): all its loads are whole vectors, and it stores only the part it owns
+    const int m_own = tm * BM, n_own = tn * BN;
+    const int m0 = (m_own + BM > p.M && p.M >= BM) ? p.M - BM : m_own;
+    const int n0 = (n_own + BN > p.N && p.N >= BN) ? p.N - BN : n_own;
 
     // ---- which part of K (loop L2, possibly split)
     const int z = blockIdx.y;
@@ -476,7 +480,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
         }
     }
 
-    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z, m0, n0);
+    store_tile<DT, TM, TN>(acc, p, m0, n0, BM, BN, wm0, wn0, lane, z, m_own, n_own);
 }
 
 // ---------------------------------------------------------------- helpers

@@ -10,6 +10,7 @@
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
 #include "gemm_kernel_reg32.hpp"
+#include "gemm_kernel_reg16.hpp"
 
 namespace mig {
 
@@ -162,6 +163,33 @@ __global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_reg(int ksteps, in
             for (int v = 0; v < T::ACC; ++v) acc[i][j][v] = 0;
     for (int it = 0; it < ksteps; ++it) {
         Micro::mma(fa, fb, acc);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    solo_finish(acc);
+}
+
+// register-direct kernels for 16- and 8-bit inputs (gemm_kernel_reg16.hpp): the operands of one K step
+// stay in registers; every pass repeats the register transposes of A and the MFMAs
+template <class T>
+__global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_reg16(int ksteps, int fill)
+{
+    typedef Reg16Micro<T> Micro;
+    typename Micro::step x;
+#pragma unroll
+    for (int t = 0; t < T::KCH; ++t) x.a[t] = solo_word<T::ES>((uint32_t)(threadIdx.x * 64 + t) * 4u, fill);
+#pragma unroll
+    for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) x.b[j][w] = solo_word<T::ES>((uint32_t)(threadIdx.x * 64 + 32 + 4 * j + w) * 4u, fill);
+    typename Micro::accv acc[T::TM][T::TN];
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < T::ACC; ++v) acc[i][j][v] = 0;
+    for (int it = 0; it < ksteps; ++it) {
+        Micro::mma(x, acc);
         __builtin_amdgcn_sched_barrier(0);
     }
     solo_finish(acc);

@@ -5,6 +5,7 @@
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
 #include "gemm_kernel_reg32.hpp"
+#include "gemm_kernel_reg16.hpp"
 #include "gemm_solo.hpp"
 #include "gemm_table.h"
 
@@ -143,6 +144,28 @@ static constexpr KernelInfo info_reg32(const char *name, int prio, int eff_pct, 
 }
 
 template <class T>
+static hipError_t launch_tile_reg16(const Params &p, hipStream_t stream)
+{
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL(gemm_kernel_reg16<T>, grid, dim3(T::NT), 0, stream, p);   // its LDS is static
+    return hipGetLastError();
+}
+template <class T>
+static hipError_t solo_reg16(int wg, int ks, int fill, hipStream_t st)
+{
+    hipLaunchKernelGGL(solo_kernel_reg16<T>, dim3((unsigned)wg), dim3(T::NT), 0, st, ks, fill);
+    return hipGetLastError();
+}
+template <class T>
+static constexpr KernelInfo info_reg16(const char *name, int prio, int eff_pct, int step_ns, int setup_ns,
+                                       int waves_per_simd)
+{
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg16<T>, prio, eff_pct, step_ns, setup_ns,
+                      &solo_reg16<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
+                      9.5e6 - (T::WAVES_K > 1 ? 1.0e6 : 0.0), 30};
+}
+
+template <class T>
 static constexpr KernelInfo info(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile<T>, prio, eff_pct, floor_ns, setup_ns,
@@ -192,6 +215,9 @@ static const KernelInfo k_f16[] = {
     info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 0, 82, 1800, 1500),
     info_dma16<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma16", 1, 87, 1700, 1500),
     info_dma16<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma16", 1, 75, 850, 1500),
+    info_reg16<Reg16Tile<F16, 2, 2, 2, 1, 6, 2>>("f16_64x64_w32x32_reg", 0, 40, 250, 300, 3),
+    info_reg16<Reg16Tile<F16, 2, 1, 1, 4, 6, 2>>("f16_32x32_k4_reg", 0, 40, 250, 600, 3),
+    info_reg16<Reg16Tile<F16, 2, 1, 1, 8, 6, 1>>("f16_32x32_k8_reg", 0, 40, 250, 900, 3),
 };
 static const KernelInfo k_bf16[] = {
     info<BF16_256x256>("bf16_256x256_w128x128", 0, 50, 2500, 1500),
@@ -201,6 +227,9 @@ static const KernelInfo k_bf16[] = {
     info_dma<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma", 0, 82, 1800, 1500),
     info_dma16<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma16", 1, 87, 1700, 1500),
     info_dma16<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma16", 1, 75, 850, 1500),
+    info_reg16<Reg16Tile<BF16, 2, 2, 2, 1, 6, 2>>("bf16_64x64_w32x32_reg", 0, 40, 250, 300, 3),
+    info_reg16<Reg16Tile<BF16, 2, 1, 1, 4, 6, 2>>("bf16_32x32_k4_reg", 0, 40, 250, 600, 3),
+    info_reg16<Reg16Tile<BF16, 2, 1, 1, 8, 6, 1>>("bf16_32x32_k8_reg", 0, 40, 250, 900, 3),
 };
 static const KernelInfo k_i8[] = {
     info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500, 1500),
@@ -210,6 +239,10 @@ static const KernelInfo k_i8[] = {
     info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 0, 75, 1800, 1500),
     info_dma16<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma16", 1, 80, 1700, 1500),
     info_dma16<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma16", 1, 65, 850, 1500),
+    info_reg16<Reg16Tile<I8, 2, 2, 2, 1, 3, 2>>("i8_128x64_w64x32_reg", 0, 40, 400, 300, 3),
+    info_reg16<Reg16Tile<I8, 2, 1, 1, 4, 3, 2>>("i8_64x32_k4_reg", 0, 40, 400, 600, 3),
+    info_reg16<Reg16Tile<I8, 2, 1, 1, 8, 3, 1>>("i8_64x32_k8_reg", 0, 40, 400, 900, 3),
+    info_reg16<Reg16Tile<I8, 1, 1, 1, 4, 3, 2>>("i8_64x16_k4_reg", 0, 40, 350, 600, 3),
 };
 
 int kernel_count(int dtype)
