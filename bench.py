@@ -11,7 +11,8 @@ The headline value is the throughput of the timed steps in TFLOP/s
   * "per_shape": each configuration's own rate (fp32 squares, fp16 squares,
     int8 shapes, the six headline im2row shapes), % of the data type's peak,
   * "im2row_models": all 20 ResNet50 v1.5 and 9 VGG16 im2row GEMMs of the paper's
-    tables with the per-model time summed over the layers that share a shape,
+    tables with the per-model time summed over the layers that share a shape
+    (fp32 as in the paper; the same shapes in fp16 and int8 under "<model>_f16" / "_i8"),
   * "solo_mode": the micro-kernel of each data type's large tile run alone on
     LDS-resident random operands - the ceiling this machine sustains,
   * "cpu_baseline": the CPU oracle timed on a bounded slice of the 4096^3 case.
@@ -276,22 +277,26 @@ def main():
             torch.cuda.empty_cache()
         result["per_shape"] = rows
 
-        # ---------------- second workload: every im2row GEMM of the paper's two tables (fp32, column-major,
-        # batch 1), and the per-model totals weighted by how many layers share each shape
+        # ---------------- second workload: every im2row GEMM of the paper's two tables (column-major, batch 1;
+        # fp32 as in the paper, then the same shapes in fp16 and int8), and the per-model totals weighted by
+        # how many layers share each shape
         models = {}
-        for model, shapes, mult in (("resnet50_v1.5", wl.RESNET50_IM2ROW, wl.RESNET50_MULTIPLICITY),
-                                    ("vgg16", wl.VGG16_IM2ROW, wl.VGG16_MULTIPLICITY)):
-            kept, rows = rows, []
-            for i, (M, N, K) in enumerate(shapes):
-                measure(model, Case("f32", "col", M, N, K, 1.0, 0.0, 6000 + i), min_ms=15.0)
-            layers, rows = rows, kept
-            total_us = sum(m * r["us"] for m, r in zip(mult, layers))
-            total_flop = sum(m * 2.0 * r["M"] * r["N"] * r["K"] for m, r in zip(mult, layers))
-            models[model] = {"conv_layers": int(sum(mult)), "distinct_shapes": len(shapes),
-                             "sum_us": round(total_us, 1), "tflops": round(total_flop / total_us / 1e6, 2),
-                             "pct_peak": round(100.0 * total_flop / total_us / 1e6 / PEAK["f32"], 2),
-                             "layers": [{k: r[k] for k in ("M", "N", "K", "kernel", "split", "us", "tflops")}
-                                        for r in layers]}
+        for dtype in ("f32", "f16", "i8"):
+            one, zero = (1, 0) if dtype == "i8" else (1.0, 0.0)
+            for model, shapes, mult in (("resnet50_v1.5", wl.RESNET50_IM2ROW, wl.RESNET50_MULTIPLICITY),
+                                        ("vgg16", wl.VGG16_IM2ROW, wl.VGG16_MULTIPLICITY)):
+                kept, rows = rows, []
+                for i, (M, N, K) in enumerate(shapes):
+                    measure(model, Case(dtype, "col", M, N, K, one, zero, 6000 + i), min_ms=15.0)
+                layers, rows = rows, kept
+                total_us = sum(m * r["us"] for m, r in zip(mult, layers))
+                total_flop = sum(m * 2.0 * r["M"] * r["N"] * r["K"] for m, r in zip(mult, layers))
+                models[model if dtype == "f32" else model + "_" + dtype] = {
+                    "dtype": dtype, "conv_layers": int(sum(mult)), "distinct_shapes": len(shapes),
+                    "sum_us": round(total_us, 1), "tflops": round(total_flop / total_us / 1e6, 2),
+                    "pct_peak": round(100.0 * total_flop / total_us / 1e6 / PEAK[dtype], 2),
+                    "layers": [{k: r[k] for k in ("M", "N", "K", "kernel", "split", "us", "tflops")} for r in layers]}
+            torch.cuda.empty_cache()
         result["im2row_models"] = models
 
         # ---------------- solo mode: the micro-kernel of each data type's large-problem tile alone

@@ -153,8 +153,9 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
 /* The selector's timing model (the counterpart of the analytical blocking model
  * the paper cites in Sec. "Blocked algorithms for GEMM"): the time in
  * microseconds it predicts for tile configuration `id` with K split `split` on
- * the canonical (column-major) problem M x N x K with 16-byte aligned operand
- * rows, launch included.  Pure host computation.  Returns a negative value for an unknown dtype or id, or M, N, K
+ * the canonical (column-major) problem M x N x K with tight leading dimensions
+ * and 16-byte aligned base addresses (as gemm_select assumes), launch included.
+ * Pure host computation.  Returns a negative value for an unknown dtype or id, or M, N, K
  * or split that are not positive. */
 double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int split);
 

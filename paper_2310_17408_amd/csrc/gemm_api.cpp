@@ -430,7 +430,10 @@ double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int s
 {
     const KernelInfo *ki = (dtype >= 0 && dtype < NUM_DTYPES) ? kernel_info(dtype, id) : nullptr;
     if (!ki || M <= 0 || N <= 0 || K <= 0 || split <= 0 || M > INT_MAX || N > INT_MAX || K > INT_MAX) return -1.0;
-    return predict_us(dtype, ki, M, N, K, split);
+    // as gemm_select for a column-major problem: tight leading dimensions, aligned base addresses
+    static const int es[NUM_DTYPES] = {4, 2, 1, 2};
+    const bool aligned = (M * es[dtype]) % 16 == 0 && (K * es[dtype]) % 16 == 0;
+    return predict_us(dtype, ki, M, N, K, split, aligned);
 }
 
 int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *stream)

@@ -158,11 +158,11 @@ static hipError_t solo_reg16(int wg, int ks, int fill, hipStream_t st)
 }
 template <class T>
 static constexpr KernelInfo info_reg16(const char *name, int prio, int eff_pct, int step_ns, int setup_ns,
-                                       int waves_per_simd)
+                                       int waves_per_simd, double fill_bytes_per_us)
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg16<T>, prio, eff_pct, step_ns, setup_ns,
                       &solo_reg16<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
-                      9.5e6 - (T::WAVES_K > 1 ? 1.0e6 : 0.0), 30};
+                      fill_bytes_per_us, 30};
 }
 
 template <class T>
@@ -210,39 +210,36 @@ static const KernelInfo k_f32[] = {
 static const KernelInfo k_f16[] = {
     info<F16_256x256>("f16_256x256_w128x128", 0, 50, 2500, 1500),
     info<F16_128x128>("f16_128x128_w64x64", 0, 47, 1700, 1500),
-    info<F16_64x64>("f16_64x64_w32x32", 1, 40, 600, 1500),
+    info<F16_64x64>("f16_64x64_w32x32", 1, 30, 700, 1500),
     info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 0, 72, 880, 1500),
     info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 0, 82, 1800, 1500),
-    info_dma16<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma16", 1, 87, 1700, 1500),
-    info_dma16<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma16", 1, 75, 850, 1500),
-    info_reg16<Reg16Tile<F16, 2, 2, 2, 1, 6, 2>>("f16_64x64_w32x32_reg", 0, 40, 250, 300, 3),
-    info_reg16<Reg16Tile<F16, 2, 1, 1, 4, 6, 2>>("f16_32x32_k4_reg", 0, 40, 250, 600, 3),
-    info_reg16<Reg16Tile<F16, 2, 1, 1, 8, 6, 1>>("f16_32x32_k8_reg", 0, 40, 250, 900, 3),
+    info_dma16<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma16", 1, 87, 1700, 3000),
+    info_dma16<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma16", 1, 75, 850, 3000),
+    info_reg16<Reg16Tile<F16, 2, 2, 2, 1, 6, 2>>("f16_64x64_w32x32_reg", 1, 20, 300, 1200, 1, 12.5e6),
+    info_reg16<Reg16Tile<F16, 2, 1, 1, 4, 6, 2>>("f16_32x32_k4_reg", 1, 20, 350, 900, 1, 11.0e6),
 };
 static const KernelInfo k_bf16[] = {
     info<BF16_256x256>("bf16_256x256_w128x128", 0, 50, 2500, 1500),
     info<BF16_128x128>("bf16_128x128_w64x64", 0, 47, 1700, 1500),
-    info<BF16_64x64>("bf16_64x64_w32x32", 1, 40, 600, 1500),
+    info<BF16_64x64>("bf16_64x64_w32x32", 1, 30, 700, 1500),
     info_dma<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma", 0, 72, 880, 1500),
     info_dma<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma", 0, 82, 1800, 1500),
-    info_dma16<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma16", 1, 87, 1700, 1500),
-    info_dma16<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma16", 1, 75, 850, 1500),
-    info_reg16<Reg16Tile<BF16, 2, 2, 2, 1, 6, 2>>("bf16_64x64_w32x32_reg", 0, 40, 250, 300, 3),
-    info_reg16<Reg16Tile<BF16, 2, 1, 1, 4, 6, 2>>("bf16_32x32_k4_reg", 0, 40, 250, 600, 3),
-    info_reg16<Reg16Tile<BF16, 2, 1, 1, 8, 6, 1>>("bf16_32x32_k8_reg", 0, 40, 250, 900, 3),
+    info_dma16<DmaTile<BF16, 256, 256, 2, 4, 4, 2, 1>>("bf16_256x256_w128x64_dma16", 1, 87, 1700, 3000),
+    info_dma16<DmaTile<BF16, 128, 128, 2, 2, 4, 2, 2>>("bf16_128x128_w64x64_dma16", 1, 75, 850, 3000),
+    info_reg16<Reg16Tile<BF16, 2, 2, 2, 1, 6, 2>>("bf16_64x64_w32x32_reg", 1, 20, 300, 1200, 1, 12.5e6),
+    info_reg16<Reg16Tile<BF16, 2, 1, 1, 4, 6, 2>>("bf16_32x32_k4_reg", 1, 20, 350, 900, 1, 11.0e6),
 };
 static const KernelInfo k_i8[] = {
     info<I8_256x256>("i8_256x256_w128x128", 0, 35, 2500, 1500),
     info<I8_128x128>("i8_128x128_w64x64", 0, 47, 800, 1500),
-    info<I8_64x64>("i8_64x64_w32x32", 1, 30, 600, 1500),
+    info<I8_64x64>("i8_64x64_w32x32", 1, 25, 1000, 2000),
     info_dma<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma", 0, 62, 880, 1500),
     info_dma<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma", 0, 75, 1800, 1500),
-    info_dma16<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma16", 1, 80, 1700, 1500),
-    info_dma16<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma16", 1, 65, 850, 1500),
-    info_reg16<Reg16Tile<I8, 2, 2, 2, 1, 3, 2>>("i8_128x64_w64x32_reg", 0, 40, 400, 300, 3),
-    info_reg16<Reg16Tile<I8, 2, 1, 1, 4, 3, 2>>("i8_64x32_k4_reg", 0, 40, 400, 600, 3),
-    info_reg16<Reg16Tile<I8, 2, 1, 1, 8, 3, 1>>("i8_64x32_k8_reg", 0, 40, 400, 900, 3),
-    info_reg16<Reg16Tile<I8, 1, 1, 1, 4, 3, 2>>("i8_64x16_k4_reg", 0, 40, 350, 600, 3),
+    info_dma16<DmaTile<I8, 256, 256, 2, 4, 4, 2, 1>>("i8_256x256_w128x64_dma16", 1, 80, 1700, 3000),
+    info_dma16<DmaTile<I8, 128, 128, 2, 2, 4, 2, 2>>("i8_128x128_w64x64_dma16", 1, 65, 850, 3000),
+    info_reg16<Reg16Tile<I8, 2, 2, 2, 1, 3, 2>>("i8_128x64_w64x32_reg", 1, 20, 400, 1200, 1, 9.5e6),
+    info_reg16<Reg16Tile<I8, 2, 1, 1, 4, 3, 2>>("i8_64x32_k4_reg", 1, 20, 700, 1200, 1, 7.0e6),
+    info_reg16<Reg16Tile<I8, 1, 1, 1, 4, 3, 2>>("i8_64x16_k4_reg", 1, 20, 450, 900, 1, 9.5e6),
 };
 
 int kernel_count(int dtype)
