@@ -8,7 +8,9 @@ GPU package.
 The arithmetic lives in ``ref_gemm.c`` (a triple loop in fp64 / int64 that
 follows the definition of the product in the paper's Sec. II-A and the
 alpha/beta form of its reference micro-kernel).  This module only compiles
-that file with gcc and marshals numpy arrays into it.
+that file with gcc and marshals numpy arrays into it.  ``ref_conv.c`` holds the
+im2row transform and the convolution the paper's rectangular GEMMs come from
+(Sec. "Rectangular Matrices"), written out directly over the image.
 """
 from .ref import (  # noqa: F401
     build,
@@ -21,6 +23,9 @@ from .ref import (  # noqa: F401
     gemm_i8,
     gemm_ex,
     gemm_sample,
+    conv_output_shape,
+    im2row_f32,
+    conv2d_nhwc_f32,
     wrap_int32,
     normalised_error,
 )

@@ -14,6 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ref_gemm.c")
+_SRC_CONV = os.path.join(_HERE, "ref_conv.c")
 _LIB = os.path.join(_HERE, "libref_gemm.so")
 _lib = None
 
@@ -21,11 +22,11 @@ _LAYOUT = {"col": 0, "row": 1}
 
 
 def build(force=False):
-    """Compile ref_gemm.c into libref_gemm.so next to it (gcc -O2 -fopenmp)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile ref_gemm.c and ref_conv.c into libref_gemm.so next to them (gcc -O2 -fopenmp)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_CONV)):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-o", tmp, _SRC, _SRC_CONV, "-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -52,6 +53,10 @@ def _load():
         lib.ref_bfloat16_to_double.restype = dbl
         lib.ref_bfloat16_to_double.argtypes = [ctypes.c_uint16]
         lib.ref_num_threads.restype = ctypes.c_int
+        lib.ref_im2row_f32.restype = ctypes.c_int
+        lib.ref_im2row_f32.argtypes = [i64] * 10 + [vp, vp]
+        lib.ref_conv2d_nhwc_f32.restype = ctypes.c_int
+        lib.ref_conv2d_nhwc_f32.argtypes = [i64] * 11 + [f32, vp, vp, f32, vp, vp]
         _lib = lib
     return _lib
 
@@ -162,6 +167,47 @@ def gemm_sample(dtype, layout, K, alpha, A, lda, B, ldb, beta, C, ldc, rows, col
         raise ValueError("beta != 0 needs C")
     rc = _load().ref_gemm_sample(code, _LAYOUT[layout], K, float(alpha), _ptr(A), lda, _ptr(B), ldb,
                                  float(beta), _ptr(C), ldc, rows.size, _ptr(rows), _ptr(cols), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    return out
+
+
+def conv_output_shape(H, W, kh, kw, stride, pad):
+    """(Hout, Wout) of a convolution; stride and pad are (vertical, horizontal) pairs."""
+    return (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
+
+
+def im2row_f32(x, kh, kw, stride, pad):
+    """The im2row matrix (batch*Hout*Wout, kh*kw*Cin) of a float32 channels-last tensor x[batch, H, W, Cin]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    batch, H, W, Cin = x.shape
+    Hout, Wout = conv_output_shape(H, W, kh, kw, stride, pad)
+    out = np.zeros((batch * Hout * Wout, kh * kw * Cin), dtype=np.float32)
+    rc = _load().ref_im2row_f32(batch, H, W, Cin, kh, kw, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    return out
+
+
+def conv2d_nhwc_f32(x, w, stride, pad, alpha=1.0, beta=0.0, y_old=None):
+    """alpha * conv(x[batch,H,W,Cin], w[kh,kw,Cin,Cout]) + beta * y_old as float64 [batch,Hout,Wout,Cout]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    batch, H, W, Cin = x.shape
+    kh, kw, cin2, Cout = w.shape
+    if cin2 != Cin:
+        raise ValueError("filter and input disagree on Cin")
+    Hout, Wout = conv_output_shape(H, W, kh, kw, stride, pad)
+    if y_old is None:
+        if beta != 0:
+            raise ValueError("beta != 0 needs y_old")
+    else:
+        y_old = np.ascontiguousarray(y_old, dtype=np.float32)
+        if y_old.shape != (batch, Hout, Wout, Cout):
+            raise ValueError("y_old has the wrong shape")
+    out = np.zeros((batch, Hout, Wout, Cout), dtype=np.float64)
+    rc = _load().ref_conv2d_nhwc_f32(batch, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1],
+                                     alpha, _ptr(x), _ptr(w), beta, _ptr(y_old), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle returned %d" % rc)
     return out

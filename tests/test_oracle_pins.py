@@ -7,6 +7,7 @@ exact small-integer arithmetic in Python ints, int8 extremes, numpy's float16
 for every binary16 pattern, torch.matmul in float64 / int64, and algebraic
 invariants (K-split, zero padding, linearity in alpha, layout transposition).
 """
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -468,3 +469,97 @@ def test_transposed_operands_exact_rational_and_against_plain(layout, ta, tb):
         zero = 0 if dtype == "i8" else np.float32(0)
         got = oracle.gemm_ex(dtype, layout, ta, tb, M, N, K, 1, A, lda, B, ldb, 0, None, 0)
         assert np.array_equal(got, plain(layout, M, N, K, one, A0, lda0, B0, ldb0, zero, None, 0))
+
+
+# ------------------------------------------------------------ convolution / im2row (oracle/ref_conv.c)
+def test_conv_worked_examples_by_hand():
+    """3 x 3 image 0..8, one channel.  2 x 2 filter [[1,2],[3,4]], no flip:
+    stride 1, no padding: out[0,0] = 0*1 + 1*2 + 3*3 + 4*4 = 27, out[0,1] = 1+4+12+20 = 37,
+    out[1,0] = 3+8+18+28 = 57, out[1,1] = 4+10+21+32 = 67;
+    stride 2, padding 1 (taps outside the image are zero): out[0,0] = x[0,0]*4 = 0,
+    out[0,1] = x[0,1]*3 + x[0,2]*4 = 11, out[1,0] = x[1,0]*2 + x[2,0]*4 = 30, out[1,1] = 4+10+21+32 = 67."""
+    x = np.arange(9, dtype=np.float32).reshape(1, 3, 3, 1)
+    w = np.array([[1, 2], [3, 4]], dtype=np.float32).reshape(2, 2, 1, 1)
+    assert np.array_equal(oracle.conv2d_nhwc_f32(x, w, (1, 1), (0, 0))[0, :, :, 0], [[27, 37], [57, 67]])
+    assert np.array_equal(oracle.conv2d_nhwc_f32(x, w, (2, 2), (1, 1))[0, :, :, 0], [[0, 11], [30, 67]])
+    # the im2row matrix of the first case, row (oh, ow), column (r, s)
+    assert np.array_equal(oracle.im2row_f32(x, 2, 2, (1, 1), (0, 0)),
+                          [[0, 1, 3, 4], [1, 2, 4, 5], [3, 4, 6, 7], [4, 5, 7, 8]])
+    # alpha and beta: 2 * conv - 1 * old
+    old = np.full((1, 2, 2, 1), 10, dtype=np.float32)
+    assert np.array_equal(oracle.conv2d_nhwc_f32(x, w, (1, 1), (0, 0), 2.0, -1.0, old)[0, :, :, 0], [[44, 64], [104, 124]])
+    # beta == 0 does not read the old output
+    bad = np.full((1, 2, 2, 1), np.nan, dtype=np.float32)
+    assert np.array_equal(oracle.conv2d_nhwc_f32(x, w, (1, 1), (0, 0), 1.0, 0.0, bad)[0, :, :, 0], [[27, 37], [57, 67]])
+
+
+def test_conv_shapes_of_the_papers_table():
+    """The layer geometries give the (m, n, k) the paper prints (Table "resnet50")."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "resnet50_v1.5_conv_geometry.txt")
+    rows = [[int(t) for t in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) == 6
+    for H, W, Cin, Cout, kh, kw, stride, pad, m, n, k in rows:
+        Hout, Wout = oracle.conv_output_shape(H, W, kh, kw, (stride, stride), (pad, pad))
+        assert (Hout * Wout, Cout, kh * kw * Cin) == (m, n, k)
+    assert [(r[8], r[9], r[10]) for r in rows] == list(wl.IM2ROW_HEADLINE)
+    # and the transform produces a matrix of that shape (a small-channel instance of the first row)
+    x = np.zeros((1, 224, 224, 3), dtype=np.float32)
+    assert oracle.im2row_f32(x, 7, 7, (2, 2), (3, 3)).shape == (12544, 147)
+
+
+@pytest.mark.parametrize("stride,pad", [((1, 1), (0, 0)), ((2, 1), (1, 2)), ((3, 2), (2, 0))])
+def test_conv_single_one_input_returns_the_filter(stride, pad):
+    """An image that is zero except for one element equal to 1 at (i0, j0, c0): the output at (oh, ow, co)
+    is filter[i0 - oh*sh + ph][j0 - ow*sw + pw][c0][co] where those indices exist, else 0."""
+    H, W, Cin, Cout, kh, kw = 7, 6, 3, 4, 3, 2
+    rng = np.random.default_rng(77)
+    w = rng.standard_normal((kh, kw, Cin, Cout)).astype(np.float32)
+    Hout, Wout = oracle.conv_output_shape(H, W, kh, kw, stride, pad)
+    for (i0, j0, c0) in ((0, 0, 0), (3, 2, 1), (6, 5, 2)):
+        x = np.zeros((1, H, W, Cin), dtype=np.float32)
+        x[0, i0, j0, c0] = 1
+        got = oracle.conv2d_nhwc_f32(x, w, stride, pad)
+        want = np.zeros((1, Hout, Wout, Cout))
+        for oh in range(Hout):
+            for ow in range(Wout):
+                r, s = i0 - oh * stride[0] + pad[0], j0 - ow * stride[1] + pad[1]
+                if 0 <= r < kh and 0 <= s < kw:
+                    want[0, oh, ow] = w[r, s, c0]
+        assert np.array_equal(got, want)
+
+
+def test_conv_all_ones_counts_the_taps_inside_the_image():
+    H, W, Cin, Cout, kh, kw, stride, pad = 6, 5, 4, 2, 3, 3, (1, 2), (1, 1)
+    x = np.ones((2, H, W, Cin), dtype=np.float32)
+    w = np.ones((kh, kw, Cin, Cout), dtype=np.float32)
+    got = oracle.conv2d_nhwc_f32(x, w, stride, pad)
+    Hout, Wout = oracle.conv_output_shape(H, W, kh, kw, stride, pad)
+    for oh in range(Hout):
+        for ow in range(Wout):
+            rows = sum(1 for r in range(kh) if 0 <= oh * stride[0] - pad[0] + r < H)
+            cols = sum(1 for s in range(kw) if 0 <= ow * stride[1] - pad[1] + s < W)
+            assert np.all(got[:, oh, ow, :] == rows * cols * Cin)
+
+
+def test_conv_is_the_gemm_of_the_im2row_matrix_and_matches_torch():
+    """The paper's premise: the convolution is a GEMM of the im2row matrix with the filter matrix.  Also
+    against torch's convolution in float64 (an independent implementation, channels-first)."""
+    rng = np.random.default_rng(78)
+    for (batch, H, W, Cin, Cout, kh, kw, stride, pad) in ((2, 9, 8, 5, 7, 3, 3, (1, 1), (1, 1)), (1, 11, 13, 16, 6, 5, 2, (2, 3), (2, 1)),
+                                                          (3, 6, 6, 8, 8, 1, 1, (1, 1), (0, 0)), (1, 8, 8, 4, 3, 3, 3, (2, 2), (0, 0))):
+        x = rng.standard_normal((batch, H, W, Cin)).astype(np.float32)
+        w = rng.standard_normal((kh, kw, Cin, Cout)).astype(np.float32)
+        old = rng.standard_normal((batch,) + oracle.conv_output_shape(H, W, kh, kw, stride, pad) + (Cout,)).astype(np.float32)
+        got = oracle.conv2d_nhwc_f32(x, w, stride, pad, 1.5, 0.5, old)
+        A = oracle.im2row_f32(x, kh, kw, stride, pad)
+        M, K = A.shape
+        via_gemm = oracle.gemm_f32("row", M, Cout, K, np.float32(1.5), A, K, w.reshape(K, Cout), Cout, np.float32(0.5),
+                                   old.reshape(M, Cout), Cout)
+        assert np.allclose(got.reshape(M, Cout), via_gemm, rtol=0, atol=1e-12)
+        t = torch.nn.functional.conv2d(torch.from_numpy(x).double().permute(0, 3, 1, 2),
+                                       torch.from_numpy(w).double().permute(3, 2, 0, 1), stride=stride, padding=pad)
+        want = 1.5 * t.permute(0, 2, 3, 1).numpy() + 0.5 * old.astype(np.float64)
+        assert np.allclose(got, want, rtol=0, atol=1e-12)
+        if kh == 1 and kw == 1:
+            # a 1 x 1 filter at stride 1 is the plain GEMM of the image with the filter
+            assert np.array_equal(A, x.reshape(M, K))
