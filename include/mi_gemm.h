@@ -116,6 +116,54 @@ int gemm_ex(int dtype, int layout, int transa, int transb, int64_t M, int64_t N,
             void *workspace, size_t workspace_bytes, void *stream);
 const char *gemm_ex_status_string(int status);
 
+/* Convolution through the im2row GEMM, fp32.  The paper's Sec. "Rectangular Matrices" takes the GEMM
+ * sizes of its Tables "resnet50" and "vgg16" from the im2row transform of convolution layers
+ * (m = Hout*Wout at batch 1, n = Cout, k = kh*kw*Cin) and its conclusions name convolutions as the next
+ * code to generate; it cites the transform without writing it out, so this is the usual channels-last one:
+ *   image  [batch][H][W][Cin], filter [kh][kw][Cin][Cout] (the K x N matrix B, row-major),
+ *   output [batch][Hout][Wout][Cout] (the M x N matrix C, row-major), all device pointers, dense,
+ *   Hout = (H + 2*pad_h - kh)/stride_h + 1, Wout likewise (integer division),
+ *   output[b][oh][ow][co] = alpha * sum over r < kh, s < kw, c < Cin of
+ *       image[b][oh*stride_h - pad_h + r][ow*stride_w - pad_w + s][c] * filter[r][s][c][co]
+ *       + beta * output[b][oh][ow][co]
+ *   with zeros for image positions outside [0,H) x [0,W), no filter flip; beta == 0: output is not read.
+ * When Cin is a multiple of 16 and the image is smaller than 4 GiB the GEMM kernels read the im2row
+ * matrix from the image in place (it is never formed).  Otherwise, or when the timing model expects
+ * it to be faster and the workspace has room, the matrix is written into the workspace
+ * (M*K floats) and the GEMM runs on it.  conv2d_im2row_workspace_bytes gives a workspace
+ * that suffices for either; a smaller one (or none) restricts the call to the in-place path and
+ * its K split.  Same stream, ownership and error conventions as gemm_f32: -k names the k-th argument
+ * of this list (conv2d_im2row_status_string), -18 = this geometry needs the im2row matrix and the
+ * workspace is too small for it.  Asynchronous on `stream`. */
+int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                      int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                      float alpha, const float *image, const float *filter,
+                      float beta, float *output,
+                      void *workspace, size_t workspace_bytes, void *stream);
+size_t conv2d_im2row_workspace_bytes(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh,
+                                     int64_t kw, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w);
+const char *conv2d_im2row_status_string(int status);
+
+/* Output extent and GEMM sizes of that convolution (pure host computation); any output pointer may be
+ * NULL.  Returns 0 or the -k of conv2d_im2row_f32's geometry arguments. */
+int conv2d_im2row_shape(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                        int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                        int64_t *Hout, int64_t *Wout, int64_t *M, int64_t *N, int64_t *K);
+
+/* The im2row transform on its own: matrix[M][K] (row-major, dense, device memory of M*K floats owned by
+ * the caller), row (b, oh, ow), column (r, s, c), from the same image and geometry as above.
+ * Returns 0, -k for the k-th argument of this list, or a HIP error. */
+int im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t kh, int64_t kw,
+               int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+               const float *image, float *matrix, void *stream);
+
+/* For tests and reports: restrict later conv2d_im2row_f32 calls of this process to one path
+ * (0 automatic, 1 in place when the geometry allows it, 2 through the im2row matrix); which path the
+ * last call on this thread took (0 none, 1 in place, 2 through the matrix).  gemm_force_kernel(F32, ...)
+ * and gemm_last_kernel_id / gemm_last_split apply to the GEMM inside. */
+int conv2d_im2row_force_path(int path);
+int conv2d_im2row_last_path(void);
+
 /* Upper bound of the workspace any split of the K loop may use for this
  * problem (dtype is one of MI_GEMM_F32/F16/I8/BF16); 0 if M, N or K is not positive. */
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K);

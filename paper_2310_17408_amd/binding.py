@@ -65,6 +65,19 @@ def load():
     lib.gemm_select.argtypes = [ci, ci, i64, i64, i64, sz, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.gemm_solo.restype = ci
     lib.gemm_solo.argtypes = [ci, ci, ci, ci, ci, vp]
+    lib.conv2d_im2row_f32.restype = ci
+    lib.conv2d_im2row_f32.argtypes = [i64] * 11 + [ctypes.c_float, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.conv2d_im2row_workspace_bytes.restype = sz
+    lib.conv2d_im2row_workspace_bytes.argtypes = [i64] * 11
+    lib.conv2d_im2row_status_string.restype = ctypes.c_char_p
+    lib.conv2d_im2row_status_string.argtypes = [ci]
+    lib.conv2d_im2row_shape.restype = ci
+    lib.conv2d_im2row_shape.argtypes = [i64] * 11 + [ctypes.POINTER(i64)] * 5
+    lib.im2row_f32.restype = ci
+    lib.im2row_f32.argtypes = [i64] * 10 + [vp, vp, vp]
+    lib.conv2d_im2row_force_path.restype = ci
+    lib.conv2d_im2row_force_path.argtypes = [ci]
+    lib.conv2d_im2row_last_path.restype = ci
     lib.gemm_last_kernel_id.restype = ci
     lib.gemm_last_split.restype = ci
     _lib = lib
@@ -193,3 +206,48 @@ def gemm_last_kernel_id():
 
 def gemm_last_split():
     return int(load().gemm_last_split())
+
+
+def conv2d_im2row_f32(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, alpha, image, filter, beta, output,
+                      workspace=None, stream=None, check=True):
+    ws, ws_bytes = _ws(workspace)
+    status = load().conv2d_im2row_f32(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, alpha, _addr(image),
+                                      _addr(filter), beta, _addr(output), ws, ws_bytes, _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, conv2d_im2row_status_string(status))
+    return status
+
+
+def conv2d_im2row_workspace_bytes(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w):
+    return int(load().conv2d_im2row_workspace_bytes(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w))
+
+
+def conv2d_im2row_status_string(status):
+    return load().conv2d_im2row_status_string(status).decode()
+
+
+def conv2d_im2row_shape(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w):
+    """(Hout, Wout, M, N, K) of the convolution and of its GEMM."""
+    out = [ctypes.c_int64(0) for _ in range(5)]
+    status = load().conv2d_im2row_shape(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w,
+                                        *[ctypes.byref(o) for o in out])
+    if status != 0:
+        raise GemmError(status, conv2d_im2row_status_string(status))
+    return tuple(int(o.value) for o in out)
+
+
+def im2row_f32(batch, H, W, Cin, kh, kw, stride_h, stride_w, pad_h, pad_w, image, matrix, stream=None, check=True):
+    status = load().im2row_f32(batch, H, W, Cin, kh, kw, stride_h, stride_w, pad_h, pad_w, _addr(image), _addr(matrix),
+                               _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, "im2row_f32: argument %d is illegal" % -status if status < 0 else "HIP error")
+    return status
+
+
+def conv2d_im2row_force_path(path):
+    if load().conv2d_im2row_force_path(path) != 0:
+        raise GemmError(-1, "conv2d_im2row_force_path: path must be 0, 1 or 2")
+
+
+def conv2d_im2row_last_path():
+    return int(load().conv2d_im2row_last_path())

@@ -263,6 +263,74 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
 
 uint32_t bits_of(float x) { uint32_t u; memcpy(&u, &x, 4); return u; }
 
+// ---------------------------------------------------------------------------
+// Convolution through the im2row GEMM.  The problem is the row-major GEMM
+//   output[M x N] = alpha * im2row(image)[M x K] * filter[K x N] + beta * output,
+// M = batch*Hout*Wout, N = Cout, K = kh*kw*Cin; in canonical (column-major) form the filter is
+// the M-contiguous operand and the im2row matrix the K-contiguous one.
+// ---------------------------------------------------------------------------
+struct ConvGeometry {
+    int64_t M, N, K;
+    Im2row g;
+};
+thread_local int t_conv_path = 0;
+int g_conv_forced_path = 0;
+constexpr double kIm2rowBytesPerUs = 4.0e6;    // the matrix written, then read back by the GEMM
+
+// 0, or -k for the k-th argument of conv2d_im2row_f32 (Cout is not checked when it is 0: im2row_f32)
+int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw, int64_t stride_h,
+                  int64_t stride_w, int64_t pad_h, int64_t pad_w, bool with_cout, ConvGeometry *out)
+{
+    const int64_t lim = 1 << 20;       // per extent; products are checked below
+    if (batch < 1 || batch > INT_MAX) return -1;
+    if (H < 1 || H > lim) return -2;
+    if (W < 1 || W > lim) return -3;
+    if (Cin < 1 || Cin > lim) return -4;
+    if (with_cout && (Cout < 1 || Cout > INT_MAX)) return -5;
+    if (kh < 1 || kh > lim) return -6;
+    if (kw < 1 || kw > lim) return -7;
+    if (stride_h < 1 || stride_h > lim) return -8;
+    if (stride_w < 1 || stride_w > lim) return -9;
+    if (pad_h < 0 || pad_h > lim || H + 2 * pad_h < kh) return -10;
+    if (pad_w < 0 || pad_w > lim || W + 2 * pad_w < kw) return -11;
+    const int64_t Hout = (H + 2 * pad_h - kh) / stride_h + 1, Wout = (W + 2 * pad_w - kw) / stride_w + 1;
+    const unsigned __int128 M = (unsigned __int128)batch * (unsigned __int128)(Hout * Wout);
+    const unsigned __int128 K = (unsigned __int128)(kh * kw) * (unsigned __int128)Cin;
+    if (M > (unsigned __int128)INT_MAX) return -1;
+    if (K > (unsigned __int128)INT_MAX) return -4;
+    out->M = (int64_t)M; out->N = Cout; out->K = (int64_t)K;
+    out->g = Im2row{(int)H, (int)W, (int)Cin, (int)kw, (int)stride_h, (int)stride_w, (int)pad_h, (int)pad_w, (int)Hout, (int)Wout};
+    return 0;
+}
+
+// The fused kernels read the image through 32-bit lane offsets and whole K steps inside one filter tap.
+bool conv_fused_ok(int64_t batch, const ConvGeometry &c)
+{
+    const unsigned __int128 image_bytes = (unsigned __int128)batch * c.g.H * c.g.W * (unsigned __int128)c.g.Cin * 4u;
+    return c.g.Cin % 16 == 0 && image_bytes < ((unsigned __int128)1 << 32);
+}
+
+// Best fused configuration (canonical problem N x M x K) for a workspace that holds `fit` partial tiles;
+// -1 if none.
+int conv_fused_kernel(const ConvGeometry &c, int64_t fit, double *us)
+{
+    int best = -1;
+    double best_us = 0.0;
+    const Forced f = g_forced[MI_GEMM_F32];
+    for (int id = 0; id < kernel_count(MI_GEMM_F32); ++id) {
+        const KernelInfo *ki = kernel_info(MI_GEMM_F32, id);
+        if (!ki->launch_im2row || !can_address(ki, c.N, 0)) continue;
+        if (f.id >= 0 ? id != f.id : ki->prio <= 0) continue;
+        const int s = auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit);
+        const double t = predict_us(MI_GEMM_F32, ki, c.N, c.M, c.K, s);
+        if (best < 0 || t < best_us) { best = id; best_us = t; }
+    }
+    if (us) *us = best_us;
+    return best;
+}
+
+size_t round16(size_t x) { return (x + 15) & ~(size_t)15; }
+
 }  // namespace
 
 extern "C" {
@@ -446,6 +514,159 @@ int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *str
     hipError_t e = ki->solo(workgroups, ksteps, fill, (hipStream_t)stream);
     return e == hipSuccess ? 0 : (int)e;
 }
+
+int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                      int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, float alpha, const float *image,
+                      const float *filter, float beta, float *output, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    t_conv_path = 0;
+    t_last_id = -1;
+    t_last_split = 0;
+    ConvGeometry c;
+    const int bad = conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c);
+    if (bad) return bad;
+    if (workspace != nullptr && (uintptr_t)workspace % 16 != 0) return -17;
+    if (output == nullptr) return -16;
+    if (alpha == 0.0f) {
+        // output <- beta * output: the GEMM entry point's quick path (K = 0 reads neither operand)
+        return gemm_f32(MI_GEMM_ROW_MAJOR, c.M, c.N, 0, 0.0f, nullptr, 1, nullptr, c.N, beta, output, c.N, nullptr, 0, stream);
+    }
+    if (image == nullptr) return -13;
+    if (filter == nullptr) return -14;
+    const size_t ws_bytes = workspace ? workspace_bytes : 0;
+    const size_t matrix_bytes = round16((size_t)c.M * (size_t)c.K * 4u);
+
+    // fused: the im2row matrix is never formed
+    const unsigned __int128 per = (unsigned __int128)c.M * (unsigned __int128)c.N * 4u;
+    int64_t fit = ws_bytes > 0 ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
+    if (fit > MAX_SPLIT) fit = MAX_SPLIT;
+    if (fit < 1) fit = 1;
+    double fused_us = 0.0;
+    const int fused_id = conv_fused_ok(batch, c) ? conv_fused_kernel(c, fit, &fused_us) : -1;
+    // explicit: the matrix in the workspace, then the GEMM with what is left of it
+    const bool explicit_fits = ws_bytes >= matrix_bytes;
+    bool fused = fused_id >= 0;
+    if (g_conv_forced_path == 2 || !fused) {
+        if (!explicit_fits) return -18;
+        fused = false;
+    } else if (g_conv_forced_path == 0 && explicit_fits && g_forced[MI_GEMM_F32].id < 0) {
+        const int gid = auto_kernel(MI_GEMM_F32, c.N, c.M, c.K, c.N, c.K, 1, true, false);
+        const double explicit_us = predict_us(MI_GEMM_F32, kernel_info(MI_GEMM_F32, gid), c.N, c.M, c.K, 1) + kLaunchUs +
+                                   (double)matrix_bytes * 2.0 / kIm2rowBytesPerUs;
+        if (explicit_us < fused_us) fused = false;
+    }
+
+    hipStream_t st = (hipStream_t)stream;
+    if (!fused) {
+        hipError_t e = launch_im2row_matrix(image, (float *)workspace, c.M, c.K, c.g, st);
+        if (e != hipSuccess) return (int)e;
+        const int rc = gemm_f32(MI_GEMM_ROW_MAJOR, c.M, c.N, c.K, alpha, (const float *)workspace, c.K, filter, c.N, beta,
+                                output, c.N, ws_bytes > matrix_bytes ? (char *)workspace + matrix_bytes : nullptr,
+                                ws_bytes - matrix_bytes, stream);
+        if (rc == 0) t_conv_path = 2;
+        return rc < 0 ? -17 : rc;      // the GEMM's own argument checks cannot fail here except through the workspace
+    }
+
+    const KernelInfo *ki = kernel_info(MI_GEMM_F32, fused_id);
+    const Forced f = g_forced[MI_GEMM_F32];
+    const int64_t ktiles = ceil_div(c.K, ki->BK);
+    int64_t sp = f.split >= 1 ? f.split : auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit);
+    if (sp > ktiles) sp = ktiles;
+    if (sp > fit) sp = fit;
+    if (sp < 1) sp = 1;
+    Params p;
+    memset(&p, 0, sizeof(p));
+    p.A = filter; p.B = image; p.C = output; p.ws = workspace;
+    p.lda = c.N; p.ldb = 0; p.ldc = c.N;
+    p.M = (int)c.N; p.N = (int)c.M; p.K = (int)c.K;
+    p.tiles_m = (int)ceil_div(c.N, ki->BM);
+    p.tiles_n = (int)ceil_div(c.M, ki->BN);
+    if ((int64_t)p.tiles_m * p.tiles_n > INT_MAX) return -1;
+    p.ktiles = (int)ktiles;
+    p.ktiles_per_split = (int)ceil_div(ktiles, sp);
+    p.split = (int)ceil_div(ktiles, p.ktiles_per_split);
+    p.alpha_bits = bits_of(alpha);
+    p.beta_bits = bits_of(beta);
+    p.use_beta = beta == 0.0f ? 0 : 1;
+    p.group_m = 8;
+    p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
+    p.conv = c.g;
+    hipError_t e = ki->launch_im2row(p, st);
+    if (e != hipSuccess) return (int)e;
+    if (p.split > 1) {
+        e = launch_reduce(MI_GEMM_F32, workspace, output, p.M, p.N, p.ldc, p.split, p.alpha_bits, p.beta_bits, p.use_beta, st);
+        if (e != hipSuccess) return (int)e;
+    }
+    t_last_id = fused_id;
+    t_last_split = p.split;
+    t_conv_path = 1;
+    return 0;
+}
+
+int im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t kh, int64_t kw, int64_t stride_h, int64_t stride_w,
+               int64_t pad_h, int64_t pad_w, const float *image, float *matrix, void *stream)
+{
+    ConvGeometry c;
+    int bad = conv_geometry(batch, H, W, Cin, 0, kh, kw, stride_h, stride_w, pad_h, pad_w, false, &c);
+    if (bad) return bad <= -5 ? bad + 1 : bad;       // this list has no Cout
+    if (image == nullptr) return -11;
+    if (matrix == nullptr) return -12;
+    hipError_t e = launch_im2row_matrix(image, matrix, c.M, c.K, c.g, (hipStream_t)stream);
+    return e == hipSuccess ? 0 : (int)e;
+}
+
+int conv2d_im2row_shape(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                        int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, int64_t *Hout, int64_t *Wout,
+                        int64_t *M, int64_t *N, int64_t *K)
+{
+    ConvGeometry c;
+    const int bad = conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c);
+    if (bad) return bad;
+    if (Hout) *Hout = c.g.Hout;
+    if (Wout) *Wout = c.g.Wout;
+    if (M) *M = c.M;
+    if (N) *N = c.N;
+    if (K) *K = c.K;
+    return 0;
+}
+
+size_t conv2d_im2row_workspace_bytes(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                                     int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w)
+{
+    ConvGeometry c;
+    if (conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c)) return 0;
+    // room for the im2row matrix and for the GEMM's (or the fused kernel's) partial tiles
+    return round16((size_t)c.M * (size_t)c.K * 4u) + round16(gemm_workspace_bytes(MI_GEMM_F32, c.M, c.N, c.K));
+}
+
+const char *conv2d_im2row_status_string(int status)
+{
+    static const char *const arg[] = {
+        "ok", "argument 1 (batch) is not positive or the output has too many pixels", "argument 2 (H) is out of range",
+        "argument 3 (W) is out of range", "argument 4 (Cin) is out of range or kh*kw*Cin is too large",
+        "argument 5 (Cout) is out of range", "argument 6 (kh) is out of range", "argument 7 (kw) is out of range",
+        "argument 8 (stride_h) is out of range", "argument 9 (stride_w) is out of range",
+        "argument 10 (pad_h) is negative, too large, or the padded image is lower than the filter",
+        "argument 11 (pad_w) is negative, too large, or the padded image is narrower than the filter",
+        "argument 12 (alpha) is illegal", "argument 13 (image) is NULL", "argument 14 (filter) is NULL",
+        "argument 15 (beta) is illegal", "argument 16 (output) is NULL",
+        "argument 17 (workspace) is not 16-byte aligned",
+        "argument 18 (workspace_bytes): this geometry needs the im2row matrix and the workspace is too small for it"};
+    if (status == 0) return arg[0];
+    if (status < 0 && status >= -18) return arg[-status];
+    if (status > 0) return hipGetErrorString((hipError_t)status);
+    return "unknown status";
+}
+
+int conv2d_im2row_force_path(int path)
+{
+    if (path < 0 || path > 2) return -1;
+    g_conv_forced_path = path;
+    return 0;
+}
+
+int conv2d_im2row_last_path(void) { return t_conv_path; }
 
 int gemm_last_kernel_id(void) { return t_last_id; }
 int gemm_last_split(void) { return t_last_split; }

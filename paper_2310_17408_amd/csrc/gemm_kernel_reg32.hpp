@@ -28,6 +28,12 @@
 // Rows of A or B beyond M or N are replaced by rows that exist (they only feed
 // rows and columns of C that are never stored); a partial last K step is loaded
 // element by element with zeros beyond K.  Loads need 4-byte alignment only.
+//
+// IM2ROW: the K-contiguous operand B is the im2row matrix of a channels-last image (the transform
+// the paper's Sec. "Rectangular Matrices" takes its GEMM sizes from), read from the image in place:
+// row n is an output pixel, and since Cin is a multiple of the K step, a step lies inside one filter
+// tap (r, s), whose position in the image is wave-uniform; a lane adds the offset of its pixel and
+// skips the load (zeros) where the tap falls outside the image.
 #pragma once
 #include "gemm_kernel.hpp"
 #include <type_traits>
@@ -97,7 +103,7 @@ struct RegMicro {
     }
 };
 
-template <class T>
+template <class T, bool IM2ROW = false>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params p)
 {
     constexpr int BS = T::BS, TM = T::TM, TN = T::TN, KG = T::KG, BK = T::BK, D = T::DEPTH, ACC = T::ACC;
@@ -133,7 +139,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         if (k_begin + per * BK < k_end) k_end = k_begin + per * BK;
     }
     const int klen = k_end > k_begin ? k_end - k_begin : 0;
-    const int nfull = klen / BK, tail = klen % BK;
+    const int nfull = klen / BK, tail = IM2ROW ? 0 : klen % BK;   // an im2row K range is whole steps
 
     // ---- which rows this lane reads.  Lanes whose rows lie beyond M or N read rows that exist.
     const int mrow = mw + TM * r;                              // first of the lane's TM rows of A and C
@@ -150,16 +156,41 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         for (int t = 0; t < KG; ++t) aoff[t][i] = (uint32_t)(((int64_t)(KG * g + t) * p.lda + (m - mw)) * 4);
     }
     uint32_t boff[TN];
+    int ih0[IM2ROW ? TN : 1], iw0[IM2ROW ? TN : 1];            // IM2ROW: image position of the pixel's tap (0, 0)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         int n = nw + BS * j + r;
         n = n < p.N ? n : p.N - 1;
-        boff[j] = (uint32_t)(((int64_t)(n - nw) * p.ldb + KG * g) * 4);
+        if constexpr (IM2ROW) {
+            const int per_image = p.conv.Hout * p.conv.Wout;
+            const int b = n / per_image, rem = n - b * per_image;
+            const int oh = rem / p.conv.Wout, ow = rem - oh * p.conv.Wout;
+            ih0[j] = oh * p.conv.stride_h - p.conv.pad_h;
+            iw0[j] = ow * p.conv.stride_w - p.conv.pad_w;
+            // from the address the tap (0, 0) of a pixel at (0, 0) without padding would have: never negative
+            boff[j] = (uint32_t)((((int64_t)(b * p.conv.H + oh * p.conv.stride_h) * p.conv.W + ow * p.conv.stride_w) *
+                                      p.conv.Cin + KG * g) * 4);
+        } else {
+            boff[j] = (uint32_t)(((int64_t)(n - nw) * p.ldb + KG * g) * 4);
+        }
     }
     const MIG_GLOBAL unsigned char *a_wave =
         (const MIG_GLOBAL unsigned char *)((const float *)p.A + (int64_t)k_begin * p.lda + mw);
-    const MIG_GLOBAL unsigned char *b_wave =
-        (const MIG_GLOBAL unsigned char *)((const float *)p.B + (int64_t)nw * p.ldb + k_begin);
+    // IM2ROW: the tap (tap_r, tap_s) and the channel tap_c the wave's next step starts at; b_wave points
+    // pad_h rows and pad_w pixels before that tap of pixel (0, 0) (an address that is only ever used
+    // with a lane offset that brings it inside the image)
+    int tap_r = 0, tap_s = 0, tap_c = 0;
+    const MIG_GLOBAL unsigned char *b_wave;
+    if constexpr (IM2ROW) {
+        const int tap = k_begin / p.conv.Cin;
+        tap_c = k_begin - tap * p.conv.Cin;
+        tap_r = tap / p.conv.kw;
+        tap_s = tap - tap_r * p.conv.kw;
+        b_wave = (const MIG_GLOBAL unsigned char *)((const float *)p.B +
+                 ((int64_t)(tap_r - p.conv.pad_h) * p.conv.W + (tap_s - p.conv.pad_w)) * p.conv.Cin + tap_c);
+    } else {
+        b_wave = (const MIG_GLOBAL unsigned char *)((const float *)p.B + (int64_t)nw * p.ldb + k_begin);
+    }
     const int64_t a_row = p.lda * 4, a_step = (int64_t)BK * a_row;
 
     // ---- loads of the next full K step (no bounds to check); steps are loaded in order.  The step's
@@ -194,14 +225,30 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         for (int j = 0; j < TN; ++j) {
             uint32_t o = boff[j];
             asm volatile("" : "+v"(o));
+            bool inside = true;
+            if constexpr (IM2ROW)
+                inside = (uint32_t)(ih0[j] + tap_r) < (uint32_t)p.conv.H && (uint32_t)(iw0[j] + tap_s) < (uint32_t)p.conv.W;
 #pragma unroll
             for (int c = 0; c < KG / 4; ++c) {
-                const f4u v = *(const MIG_GLOBAL f4u *)(pb + o + 16 * c);
+                f4u v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (inside) v = *(const MIG_GLOBAL f4u *)(pb + o + 16 * c);
                 xb.v[j][4 * c + 0] = v[0]; xb.v[j][4 * c + 1] = v[1]; xb.v[j][4 * c + 2] = v[2]; xb.v[j][4 * c + 3] = v[3];
             }
         }
         pa += a_step;
         pb += BK * 4;
+        if constexpr (IM2ROW) {
+            // the taps of one filter row are contiguous in the image; the next filter row is one image row on
+            tap_c += BK;
+            if (tap_c == p.conv.Cin) {
+                tap_c = 0;
+                if (++tap_s == p.conv.kw) {
+                    tap_s = 0;
+                    ++tap_r;
+                    pb += (int64_t)(p.conv.W - p.conv.kw) * p.conv.Cin * 4;
+                }
+            }
+        }
     };
     // ---- the partial last step: element by element, zeros beyond the K range
     auto load_tail = [&](aset &xa, bset &xb) {
@@ -232,7 +279,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
 
     aset fa[D], ta;
     bset fb[D], tb;
-    if (tail) load_tail(ta, tb);                               // the first loads to be issued
+    if constexpr (!IM2ROW)                                     // an im2row K range has no partial step
+        if (tail) load_tail(ta, tb);                           // the first loads to be issued
 
     // ---- K loop: D steps in flight.  In the steady state every load is unconditional, so the
     // number of loads outstanding is fixed and each MFMA group waits for exactly its own operands.

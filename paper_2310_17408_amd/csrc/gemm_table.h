@@ -5,6 +5,15 @@
 
 namespace mig {
 
+// Geometry of a convolution whose im2row matrix is the canonical B (one row per output pixel, K =
+// kh*kw*Cin contiguous), read from the channels-last image in place: row n = (b, oh, ow), column
+// k = (r, s, c) is image[b][oh*stride_h - pad_h + r][ow*stride_w - pad_w + s][c], zero outside the image.
+struct Im2row {
+    int H, W, Cin, kw;
+    int stride_h, stride_w, pad_h, pad_w;
+    int Hout, Wout;
+};
+
 // One canonical problem (C column-major, A with M contiguous, B with K contiguous)
 // and how the grid covers it.
 struct Params {
@@ -24,6 +33,7 @@ struct Params {
     int a_kc, b_nc;        // transposed operands: A has K contiguous / B has N contiguous (staged kernels only)
     int group_m;           // tiles per column group in the tile order
     int xcd_remap;         // deal contiguous tile ranges to the 8 XCDs
+    Im2row conv;           // implicit-im2row launches only: B is the image, ldb is unused
 };
 
 struct KernelInfo {
@@ -55,6 +65,8 @@ struct KernelInfo {
     // direct ones stage every tile through registers.
     int unaligned_pct;
     int transposed_ok;       // takes A with K contiguous and B with N contiguous as well (Params::a_kc, b_nc)
+    // the same configuration with B read through the im2row map of Params::conv (nullptr: not built)
+    hipError_t (*launch_im2row)(const Params &, hipStream_t);
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8, 3 bf16
@@ -62,6 +74,9 @@ const KernelInfo *kernel_info(int dtype, int id);  // nullptr if out of range
 
 hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
                          uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream);
+// The im2row matrix [rows][K] (row-major, K = kh*kw*Cin, kh given by K) of a channels-last fp32 image.
+hipError_t launch_im2row_matrix(const float *image, float *matrix, int64_t rows, int64_t K, const Im2row &g,
+                                hipStream_t stream);
 hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
                         hipStream_t stream);
 

@@ -128,6 +128,13 @@ static hipError_t launch_tile_reg32(const Params &p, hipStream_t stream)
     return hipGetLastError();
 }
 template <class T>
+static hipError_t launch_tile_reg32_im2row(const Params &p, hipStream_t stream)
+{
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL((gemm_kernel_reg32<T, true>), grid, dim3(T::NT), 0, stream, p);
+    return hipGetLastError();
+}
+template <class T>
 static hipError_t solo_reg32(int wg, int ks, int fill, hipStream_t st)
 {
     hipLaunchKernelGGL(solo_kernel_reg<T>, dim3((unsigned)wg), dim3(T::NT), 0, st, ks, fill);
@@ -140,7 +147,8 @@ static constexpr KernelInfo info_reg32(const char *name, int prio, int eff_pct, 
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg32<T>, prio, eff_pct, step_ns, setup_ns,
                       &solo_reg32<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
-                      (T::WM * T::WN <= 256 ? 12.5e6 : 9.5e6) - (T::WAVES_K > 1 ? 1.0e6 : 0.0)};
+                      (T::WM * T::WN <= 256 ? 12.5e6 : 9.5e6) - (T::WAVES_K > 1 ? 1.0e6 : 0.0), 0, 0,
+                      &launch_tile_reg32_im2row<T>};
 }
 
 template <class T>
@@ -277,6 +285,13 @@ hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64
     else
         hipLaunchKernelGGL(reduce_kernel<float>, dim3(g), dim3(256), 0, stream, (const float *)ws, (float *)C, M, N,
                            ldc, split, alpha_bits, beta_bits, use_beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_im2row_matrix(const float *image, float *matrix, int64_t rows, int64_t K, const Im2row &g,
+                                hipStream_t stream)
+{
+    hipLaunchKernelGGL(im2row_matrix_kernel, dim3(blocks_for(rows * K)), dim3(256), 0, stream, image, matrix, rows, K, g);
     return hipGetLastError();
 }
 

@@ -157,3 +157,29 @@ def test_gemm_ex_argument_errors():
     one = ctypes.c_float(1.0)
     assert lib.gemm_ex(0, 0, 0, 0, 8, 6, 4, None, P, 8, P, 4, ctypes.byref(one), P, 8, None, 0, None) == -8
     assert lib.gemm_ex(0, 0, 0, 0, 8, 6, 4, ctypes.byref(one), P, 8, P, 4, None, P, 8, None, 0, None) == -13
+
+
+def test_conv_geometry_and_argument_errors():
+    """conv2d_im2row_f32 / im2row_f32: shapes and argument checks run on the host before anything is launched."""
+    assert mg.conv2d_im2row_shape(1, 224, 224, 3, 64, 7, 7, 2, 2, 3, 3) == (112, 112, 12544, 64, 147)
+    assert mg.conv2d_im2row_shape(4, 56, 56, 64, 256, 1, 1, 1, 1, 0, 0) == (56, 56, 4 * 3136, 256, 64)
+    assert mg.conv2d_im2row_shape(1, 5, 7, 2, 3, 3, 2, 2, 3, 1, 0) == (3, 2, 6, 3, 12)
+    good = [1, 8, 8, 16, 4, 3, 3, 1, 1, 1, 1]
+    bad = {1: 0, 2: 0, 3: -1, 4: 0, 5: 0, 6: 0, 7: 0, 8: 0, 9: -2, 10: -1, 11: 1 << 21}
+    for pos, value in bad.items():
+        args = list(good)
+        args[pos - 1] = value
+        assert mg.conv2d_im2row_f32(*args, 1.0, 1 << 20, 1 << 20, 0.0, 1 << 20, check=False) == -pos
+        assert str(pos) in mg.conv2d_im2row_status_string(-pos)
+    # a filter larger than the padded image
+    assert mg.conv2d_im2row_f32(1, 4, 8, 16, 4, 7, 3, 1, 1, 1, 1, 1.0, 1 << 20, 1 << 20, 0.0, 1 << 20, check=False) == -10
+    assert mg.conv2d_im2row_f32(*good, 1.0, None, 1 << 20, 0.0, 1 << 20, check=False) == -13
+    assert mg.conv2d_im2row_f32(*good, 1.0, 1 << 20, None, 0.0, 1 << 20, check=False) == -14
+    assert mg.conv2d_im2row_f32(*good, 1.0, 1 << 20, 1 << 20, 0.0, None, check=False) == -16
+    assert mg.conv2d_im2row_workspace_bytes(*good) >= 64 * 144 * 4
+    assert mg.conv2d_im2row_workspace_bytes(0, *good[1:]) == 0
+    assert mg.im2row_f32(1, 8, 8, 16, 3, 3, 1, 1, 1, 1, None, 1 << 20, check=False) == -11
+    assert mg.im2row_f32(1, 8, 8, 16, 3, 3, 1, 1, 1, 1, 1 << 20, None, check=False) == -12
+    assert mg.im2row_f32(1, 8, 8, 16, 0, 3, 1, 1, 1, 1, 1 << 20, 1 << 20, check=False) == -5
+    with pytest.raises(mg.GemmError):
+        mg.conv2d_im2row_force_path(3)

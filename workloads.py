@@ -118,3 +118,24 @@ def bf16_bits_to_f32(bits):
 def logical(layout, buf, rows, cols):
     """View the rows x cols matrix held in a buffer made by the generators above as (rows, cols)."""
     return buf[:cols, :rows].T if layout == "col" else buf[:rows, :cols]
+
+
+def conv_tensors_f32(seed, batch, H, W, Cin, Cout, kh, kw, Hout, Wout):
+    """Seeded U[-1,1) channels-last image [batch,H,W,Cin], filter [kh,kw,Cin,Cout] and old output
+    [batch,Hout,Wout,Cout] of a convolution layer (float32)."""
+    image = uniform_f32(seed, "row", batch * H * W, Cin).reshape(batch, H, W, Cin)
+    filt = uniform_f32(seed + 1, "row", kh * kw * Cin, Cout).reshape(kh, kw, Cin, Cout)
+    old = uniform_f32(seed + 2, "row", batch * Hout * Wout, Cout).reshape(batch, Hout, Wout, Cout)
+    return image, filt, old
+
+
+# Convolution geometries (H, W, Cin, Cout, kh, kw, stride, pad) of ResNet50 v1.5 layers whose im2row
+# GEMMs are the paper's six headline shapes, in the order of IM2ROW_HEADLINE.
+RESNET50_HEADLINE_CONVS = [
+    (224, 224, 3, 64, 7, 7, 2, 3),
+    (56, 56, 64, 64, 3, 3, 1, 1),
+    (56, 56, 128, 128, 3, 3, 2, 1),
+    (28, 28, 256, 256, 3, 3, 2, 1),
+    (14, 14, 512, 512, 3, 3, 2, 1),
+    (56, 56, 256, 64, 1, 1, 1, 0),
+]
