@@ -127,10 +127,10 @@ const char *gemm_ex_status_string(int status);
  *       image[b][oh*stride_h - pad_h + r][ow*stride_w - pad_w + s][c] * filter[r][s][c][co]
  *       + beta * output[b][oh][ow][co]
  *   with zeros for image positions outside [0,H) x [0,W), no filter flip; beta == 0: output is not read.
- * When Cin is a multiple of 16 and the image is smaller than 4 GiB the GEMM kernels read the im2row
- * matrix from the image in place (it is never formed).  Otherwise, or when the timing model expects
- * it to be faster and the workspace has room, the matrix is written into the workspace
- * (M*K floats) and the GEMM runs on it.  conv2d_im2row_workspace_bytes gives a workspace
+ * When the image is smaller than 2 GiB (and, unless Cin is a multiple of 16, kh*kw*Cin < 2^22) the
+ * GEMM kernels read the im2row matrix from the image in place (it is never formed).  Otherwise, or
+ * when the timing model expects it to be faster and the workspace has room, the matrix is written
+ * into the workspace (M*K floats) and the GEMM runs on it.  conv2d_im2row_workspace_bytes gives a workspace
  * that suffices for either; a smaller one (or none) restricts the call to the in-place path and
  * its K split.  Same stream, ownership and error conventions as gemm_f32: -k names the k-th argument
  * of this list (conv2d_im2row_status_string), -18 = this geometry needs the im2row matrix and the

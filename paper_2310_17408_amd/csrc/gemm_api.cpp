@@ -275,7 +275,8 @@ struct ConvGeometry {
 };
 thread_local int t_conv_path = 0;
 int g_conv_forced_path = 0;
-constexpr double kIm2rowBytesPerUs = 4.0e6;    // the matrix written, then read back by the GEMM
+// forming the matrix, measured: about 5 us plus its bytes at 1.35 TB/s (a launch, one element per thread)
+constexpr double kIm2rowFixedUs = 5.0, kIm2rowBytesPerUs = 1.35e6;
 
 // 0, or -k for the k-th argument of conv2d_im2row_f32 (Cout is not checked when it is 0: im2row_f32)
 int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw, int64_t stride_h,
@@ -303,11 +304,12 @@ int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout
     return 0;
 }
 
-// The fused kernels read the image through 32-bit lane offsets and whole K steps inside one filter tap.
+// The fused kernels read the image through 32-bit lane offsets; the element-by-element variant splits
+// k into (filter row, element of the run) in single precision, exact below 2^22.
 bool conv_fused_ok(int64_t batch, const ConvGeometry &c)
 {
     const unsigned __int128 image_bytes = (unsigned __int128)batch * c.g.H * c.g.W * (unsigned __int128)c.g.Cin * 4u;
-    return c.g.Cin % 16 == 0 && image_bytes < ((unsigned __int128)1 << 32);
+    return image_bytes < ((unsigned __int128)1 << 31) && (c.g.Cin % 16 == 0 || c.K < ((int64_t)1 << 22));
 }
 
 // Best fused configuration (canonical problem N x M x K) for a workspace that holds `fit` partial tiles;
@@ -552,8 +554,8 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
         fused = false;
     } else if (g_conv_forced_path == 0 && explicit_fits && g_forced[MI_GEMM_F32].id < 0) {
         const int gid = auto_kernel(MI_GEMM_F32, c.N, c.M, c.K, c.N, c.K, 1, true, false);
-        const double explicit_us = predict_us(MI_GEMM_F32, kernel_info(MI_GEMM_F32, gid), c.N, c.M, c.K, 1) + kLaunchUs +
-                                   (double)matrix_bytes * 2.0 / kIm2rowBytesPerUs;
+        const double explicit_us = predict_us(MI_GEMM_F32, kernel_info(MI_GEMM_F32, gid), c.N, c.M, c.K, 1) + kIm2rowFixedUs +
+                                   (double)matrix_bytes / kIm2rowBytesPerUs;
         if (explicit_us < fused_us) fused = false;
     }
 
@@ -592,7 +594,7 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
     p.group_m = 8;
     p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
     p.conv = c.g;
-    hipError_t e = ki->launch_im2row(p, st);
+    hipError_t e = (c.g.Cin % 16 == 0 ? ki->launch_im2row : ki->launch_im2row_runs)(p, st);
     if (e != hipSuccess) return (int)e;
     if (p.split > 1) {
         e = launch_reduce(MI_GEMM_F32, workspace, output, p.M, p.N, p.ldc, p.split, p.alpha_bits, p.beta_bits, p.use_beta, st);

@@ -30,10 +30,15 @@
 // element by element with zeros beyond K.  Loads need 4-byte alignment only.
 //
 // IM2ROW: the K-contiguous operand B is the im2row matrix of a channels-last image (the transform
-// the paper's Sec. "Rectangular Matrices" takes its GEMM sizes from), read from the image in place:
-// row n is an output pixel, and since Cin is a multiple of the K step, a step lies inside one filter
-// tap (r, s), whose position in the image is wave-uniform; a lane adds the offset of its pixel and
-// skips the load (zeros) where the tap falls outside the image.
+// the paper's Sec. "Rectangular Matrices" takes its GEMM sizes from), read from the image in place;
+// row n is an output pixel.
+//   IM2ROW_TAPS: Cin is a multiple of the K step, so a step lies inside one filter tap (r, s), whose
+//     position in the image is wave-uniform; a lane adds the offset of its pixel and skips the load
+//     (zeros) where the tap falls outside the image.
+//   IM2ROW_RUNS: any Cin (the first layer of a network has 3).  For one filter row r the kw*Cin
+//     elements (s, c) are one contiguous run of the image row, so k = r*(kw*Cin) + e and element e of
+//     the run is inside the image for lo <= e < hi, two bounds per pixel.  Elements are loaded one by
+//     one.
 #pragma once
 #include "gemm_kernel.hpp"
 #include <type_traits>
@@ -103,7 +108,9 @@ struct RegMicro {
     }
 };
 
-template <class T, bool IM2ROW = false>
+enum { IM2ROW_NONE = 0, IM2ROW_TAPS = 1, IM2ROW_RUNS = 2 };
+
+template <class T, int IM2ROW = IM2ROW_NONE>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params p)
 {
     constexpr int BS = T::BS, TM = T::TM, TN = T::TN, KG = T::KG, BK = T::BK, D = T::DEPTH, ACC = T::ACC;
@@ -139,7 +146,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         if (k_begin + per * BK < k_end) k_end = k_begin + per * BK;
     }
     const int klen = k_end > k_begin ? k_end - k_begin : 0;
-    const int nfull = klen / BK, tail = IM2ROW ? 0 : klen % BK;   // an im2row K range is whole steps
+    const int nfull = klen / BK, tail = IM2ROW == IM2ROW_TAPS ? 0 : klen % BK;   // whole steps when a step lies in a tap
 
     // ---- which rows this lane reads.  Lanes whose rows lie beyond M or N read rows that exist.
     const int mrow = mw + TM * r;                              // first of the lane's TM rows of A and C
@@ -156,7 +163,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         for (int t = 0; t < KG; ++t) aoff[t][i] = (uint32_t)(((int64_t)(KG * g + t) * p.lda + (m - mw)) * 4);
     }
     uint32_t boff[TN];
-    int ih0[IM2ROW ? TN : 1], iw0[IM2ROW ? TN : 1];            // IM2ROW: image position of the pixel's tap (0, 0)
+    int ih0[IM2ROW ? TN : 1], iw0[IM2ROW == IM2ROW_TAPS ? TN : 1];   // IM2ROW: image position of the pixel's tap (0, 0)
+    int run_lo[IM2ROW == IM2ROW_RUNS ? TN : 1], run_hi[IM2ROW == IM2ROW_RUNS ? TN : 1];   // part of a run inside the image
+    const int run = p.conv.kw * p.conv.Cin;                    // IM2ROW_RUNS: elements of K per filter row
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         int n = nw + BS * j + r;
@@ -166,10 +175,17 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
             const int b = n / per_image, rem = n - b * per_image;
             const int oh = rem / p.conv.Wout, ow = rem - oh * p.conv.Wout;
             ih0[j] = oh * p.conv.stride_h - p.conv.pad_h;
-            iw0[j] = ow * p.conv.stride_w - p.conv.pad_w;
+            const int iw = ow * p.conv.stride_w - p.conv.pad_w;
+            if constexpr (IM2ROW == IM2ROW_TAPS) {
+                iw0[j] = iw;
+            } else {
+                run_lo[j] = iw < 0 ? -iw * p.conv.Cin : 0;
+                const int hi = (p.conv.W - iw) * p.conv.Cin;
+                run_hi[j] = hi < run ? hi : run;
+            }
             // from the address the tap (0, 0) of a pixel at (0, 0) without padding would have: never negative
             boff[j] = (uint32_t)((((int64_t)(b * p.conv.H + oh * p.conv.stride_h) * p.conv.W + ow * p.conv.stride_w) *
-                                      p.conv.Cin + KG * g) * 4);
+                                      p.conv.Cin + (IM2ROW == IM2ROW_TAPS ? KG * g : 0)) * 4);
         } else {
             boff[j] = (uint32_t)(((int64_t)(n - nw) * p.ldb + KG * g) * 4);
         }
@@ -181,7 +197,11 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
     // with a lane offset that brings it inside the image)
     int tap_r = 0, tap_s = 0, tap_c = 0;
     const MIG_GLOBAL unsigned char *b_wave;
-    if constexpr (IM2ROW) {
+    if constexpr (IM2ROW == IM2ROW_RUNS) {
+        // pad_h rows and pad_w pixels before the image: what a pixel's offset counts from
+        b_wave = (const MIG_GLOBAL unsigned char *)((const float *)p.B -
+                 ((int64_t)p.conv.pad_h * p.conv.W + p.conv.pad_w) * p.conv.Cin);
+    } else if constexpr (IM2ROW == IM2ROW_TAPS) {
         const int tap = k_begin / p.conv.Cin;
         tap_c = k_begin - tap * p.conv.Cin;
         tap_r = tap / p.conv.kw;
@@ -197,6 +217,29 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
     // base addresses are wave-uniform and live in scalar registers, a lane adds its constant 32-bit
     // offsets (the empty asm statements keep the compiler from merging the two into per-lane
     // 64-bit pointers, which would cost registers and an addition per load).
+    // ---- IM2ROW_RUNS: the lane's KG elements of B from k = kfirst on, for each of its pixels
+    const float inv_run = 1.0f / (float)run;
+    const int row_floats = p.conv.W * p.conv.Cin;
+    int k_lane = k_begin + KG * g;                             // the lane's first k of the next step to load
+    auto load_b_runs = [&](int kfirst, bset &xb) {
+#pragma unroll
+        for (int t = 0; t < KG; ++t) {
+            const int k = kfirst + t;
+            int rr = (int)((float)k * inv_run);                // k / run, exact after the correction (k < 2^22)
+            int e = k - rr * run;
+            if (e < 0) { --rr; e += run; }
+            if (e >= run) { ++rr; e -= run; }
+            const uint32_t ko = (uint32_t)((rr * row_floats + e) * 4);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const bool inside = k < k_end && (uint32_t)(ih0[j] + rr) < (uint32_t)p.conv.H && e >= run_lo[j] && e < run_hi[j];
+                float v = 0.0f;
+                if (inside) v = *(const MIG_GLOBAL float *)(b_wave + (boff[j] + ko));
+                xb.v[j][t] = v;
+            }
+        }
+    };
+
     const MIG_GLOBAL unsigned char *pa = a_wave, *pb = b_wave;
     auto load_step = [&](auto one_by_one, aset &xa, bset &xb) {
         asm volatile("" : "+s"(pa), "+s"(pb));
@@ -221,12 +264,18 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
                 }
             }
         }
+        if constexpr (IM2ROW == IM2ROW_RUNS) {
+            load_b_runs(k_lane, xb);
+            k_lane += BK;
+            pa += a_step;
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             uint32_t o = boff[j];
             asm volatile("" : "+v"(o));
             bool inside = true;
-            if constexpr (IM2ROW)
+            if constexpr (IM2ROW == IM2ROW_TAPS)
                 inside = (uint32_t)(ih0[j] + tap_r) < (uint32_t)p.conv.H && (uint32_t)(iw0[j] + tap_s) < (uint32_t)p.conv.W;
 #pragma unroll
             for (int c = 0; c < KG / 4; ++c) {
@@ -237,7 +286,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         }
         pa += a_step;
         pb += BK * 4;
-        if constexpr (IM2ROW) {
+        if constexpr (IM2ROW == IM2ROW_TAPS) {
             // the taps of one filter row are contiguous in the image; the next filter row is one image row on
             tap_c += BK;
             if (tap_c == p.conv.Cin) {
@@ -264,9 +313,12 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
                 const uint32_t off = (uint32_t)(((int64_t)(KG * g) * p.lda + (m - mw)) * 4);
                 xa.v[t][i] = valid ? *(const MIG_GLOBAL float *)(ta_ + t * a_row + off) : 0.0f;
             }
+            if constexpr (IM2ROW == IM2ROW_NONE) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) xb.v[j][t] = valid ? *(const MIG_GLOBAL float *)(tb_ + boff[j] + 4 * t) : 0.0f;
+                for (int j = 0; j < TN; ++j) xb.v[j][t] = valid ? *(const MIG_GLOBAL float *)(tb_ + boff[j] + 4 * t) : 0.0f;
+            }
         }
+        if constexpr (IM2ROW == IM2ROW_RUNS) load_b_runs(k_begin + nfull * BK + KG * g, xb);
     };
 
     accv acc[TM][TN];
@@ -279,8 +331,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
 
     aset fa[D], ta;
     bset fb[D], tb;
-    if constexpr (!IM2ROW)                                     // an im2row K range has no partial step
-        if (tail) load_tail(ta, tb);                           // the first loads to be issued
+    if (tail) load_tail(ta, tb);                               // the first loads to be issued
 
     // ---- K loop: D steps in flight.  In the steady state every load is unconditional, so the
     // number of loads outstanding is fixed and each MFMA group waits for exactly its own operands.

@@ -65,8 +65,10 @@ struct KernelInfo {
     // direct ones stage every tile through registers.
     int unaligned_pct;
     int transposed_ok;       // takes A with K contiguous and B with N contiguous as well (Params::a_kc, b_nc)
-    // the same configuration with B read through the im2row map of Params::conv (nullptr: not built)
+    // the same configuration with B read through the im2row map of Params::conv (nullptr: not built):
+    // for Cin a multiple of the K step (a step lies in one filter tap), and for any Cin (element by element)
     hipError_t (*launch_im2row)(const Params &, hipStream_t);
+    hipError_t (*launch_im2row_runs)(const Params &, hipStream_t);
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8, 3 bf16

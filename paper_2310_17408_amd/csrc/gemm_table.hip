@@ -131,7 +131,14 @@ template <class T>
 static hipError_t launch_tile_reg32_im2row(const Params &p, hipStream_t stream)
 {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
-    hipLaunchKernelGGL((gemm_kernel_reg32<T, true>), grid, dim3(T::NT), 0, stream, p);
+    hipLaunchKernelGGL((gemm_kernel_reg32<T, IM2ROW_TAPS>), grid, dim3(T::NT), 0, stream, p);
+    return hipGetLastError();
+}
+template <class T>
+static hipError_t launch_tile_reg32_im2row_runs(const Params &p, hipStream_t stream)
+{
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL((gemm_kernel_reg32<T, IM2ROW_RUNS>), grid, dim3(T::NT), 0, stream, p);
     return hipGetLastError();
 }
 template <class T>
@@ -148,7 +155,7 @@ static constexpr KernelInfo info_reg32(const char *name, int prio, int eff_pct, 
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg32<T>, prio, eff_pct, step_ns, setup_ns,
                       &solo_reg32<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
                       (T::WM * T::WN <= 256 ? 12.5e6 : 9.5e6) - (T::WAVES_K > 1 ? 1.0e6 : 0.0), 0, 0,
-                      &launch_tile_reg32_im2row<T>};
+                      &launch_tile_reg32_im2row<T>, &launch_tile_reg32_im2row_runs<T>};
 }
 
 template <class T>

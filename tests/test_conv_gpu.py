@@ -75,11 +75,26 @@ def test_fused_path_with_k_split_and_without_workspace():
     assert sp == 1
 
 
+RUN_GEOMS = [
+    (2, 32, 30, 3, 20, 7, 7, 2, 2, 3, 3),      # Cin = 3: the first layer of both networks
+    (1, 17, 19, 5, 9, 3, 3, 1, 1, 1, 1),       # K = 45: less than three K steps
+    (1, 9, 9, 1, 17, 3, 3, 1, 1, 1, 1),        # one channel: runs shorter than a lane's share of a step
+    (1, 10, 12, 20, 33, 3, 2, 2, 1, 0, 1),     # Cin a multiple of 4 but not of 16
+]
+
+
+def test_fused_path_for_any_channel_count_on_every_register_direct_kernel():
+    """Cin that is no multiple of the K step: the run-wise reader (elements one by one, partial last step)."""
+    for kid in _fused_kernels():
+        for i, geom in enumerate(RUN_GEOMS):
+            took, got, _ = run_conv(geom, 7350 + 10 * kid + i, 1.5, 0.5, path=1, kernel_id=kid, expect_path=1)
+            assert got == kid
+        run_conv(RUN_GEOMS[0], 7390 + kid, 1.0, 0.0, path=1, kernel_id=kid, split=2, workspace="split", expect_path=1)
+
+
 def test_path_through_the_im2row_matrix():
-    # Cin = 3 (the first layer of both networks) cannot be read in place
-    run_conv((2, 32, 30, 3, 20, 7, 7, 2, 2, 3, 3), 7400, 1.0, 0.0, expect_path=2)
-    run_conv((1, 17, 19, 5, 9, 3, 3, 1, 1, 1, 1), 7401, 2.0, 1.0, expect_path=2)
-    # and a geometry the fused kernels take, forced through the matrix
+    run_conv(RUN_GEOMS[0], 7400, 1.0, 0.0, path=2, expect_path=2)
+    run_conv(RUN_GEOMS[1], 7401, 2.0, 1.0, path=2, expect_path=2)
     run_conv(GEOMS[1], 7402, 1.5, 0.5, path=2, expect_path=2)
 
 
@@ -101,7 +116,7 @@ def test_resnet50_headline_layers_at_full_size(i):
     geom = (1, H, W, Cin, Cout, kh, kw, stride, stride, pad, pad)
     assert mg.conv2d_im2row_shape(*geom)[2:] == wl.IM2ROW_HEADLINE[i]
     took, _, _ = run_conv(geom, 7600 + i)
-    assert took == (2 if Cin % 16 else 1)
+    assert took == 1
 
 
 def test_im2row_matrix_is_bit_exact():
@@ -122,8 +137,12 @@ def test_workspace_too_small_for_the_matrix_is_an_error():
     image = torch.zeros((1, 16, 16, 3), device="cuda")
     filt = torch.zeros((3, 3, 3, 8), device="cuda")
     out = torch.full((1, Hout, Wout, 8), 5.0, device="cuda")
-    assert mg.conv2d_im2row_f32(*geom, 1.0, image, filt, 0.0, out, None, check=False) == -18
-    small = torch.empty(M * K * 4 - 16, dtype=torch.uint8, device="cuda")
-    assert mg.conv2d_im2row_f32(*geom, 1.0, image, filt, 0.0, out, small, check=False) == -18
+    mg.conv2d_im2row_force_path(2)
+    try:
+        assert mg.conv2d_im2row_f32(*geom, 1.0, image, filt, 0.0, out, None, check=False) == -18
+        small = torch.empty(M * K * 4 - 16, dtype=torch.uint8, device="cuda")
+        assert mg.conv2d_im2row_f32(*geom, 1.0, image, filt, 0.0, out, small, check=False) == -18
+    finally:
+        mg.conv2d_im2row_force_path(0)
     torch.cuda.synchronize()
     assert torch.all(out == 5.0)      # nothing was launched
