@@ -13,6 +13,8 @@ The headline value is the throughput of the timed steps in TFLOP/s
   * "im2row_models": all 20 ResNet50 v1.5 and 9 VGG16 im2row GEMMs of the paper's
     tables with the per-model time summed over the layers that share a shape
     (fp32 as in the paper; the same shapes in fp16 and int8 under "<model>_f16" / "_i8"),
+  * "conv_im2row": the convolution layers behind the headline shapes and the VGG16 table, with the im2row
+    matrix read from the image in place, next to the GEMM on a matrix that already exists,
   * "solo_mode": the micro-kernel of each data type's large tile run alone on
     LDS-resident random operands - the ceiling this machine sustains,
   * "cpu_baseline": the CPU oracle timed on a bounded slice of the 4096^3 case.
@@ -298,6 +300,42 @@ def main():
                     "layers": [{k: r[k] for k in ("M", "N", "K", "kernel", "split", "us", "tflops")} for r in layers]}
             torch.cuda.empty_cache()
         result["im2row_models"] = models
+
+        # ---------------- third workload: the convolutions themselves (fp32, batch 1, channels last): the layers
+        # behind the six headline GEMM sizes and the 9 VGG16 rows through conv2d_im2row_f32, which reads the
+        # im2row matrix from the image in place; "gemm_us" is the GEMM of the same sizes on a matrix that already
+        # exists (the figure of the second workload), the difference is what the transform costs
+        gemm_us = {(r["M"], r["N"], r["K"]): r["us"] for m in ("resnet50_v1.5", "vgg16") for r in models[m]["layers"]}
+
+        class ConvCase:
+            def __init__(self, geom, seed):
+                H, W, Cin, Cout, kh, kw, stride, pad = geom
+                self.geom = (1, H, W, Cin, Cout, kh, kw, stride, stride, pad, pad)
+                Hout, Wout, self.M, self.N, self.K = mg.conv2d_im2row_shape(*self.geom)
+                image, filt, _ = wl.conv_tensors_f32(seed, 1, H, W, Cin, Cout, kh, kw, Hout, Wout)
+                self.image, self.filt = dev(image), dev(filt)
+                self.out = torch.zeros(self.M * self.N, device="cuda")
+                self.ws = torch.empty(mg.conv2d_im2row_workspace_bytes(*self.geom), dtype=torch.uint8, device="cuda")
+
+            def run(self, on=stream):
+                mg.conv2d_im2row_f32(*self.geom, 1.0, self.image, self.filt, 0.0, self.out, self.ws, on)
+
+        convs = []
+        for model, geoms in (("resnet50_v1.5", wl.RESNET50_HEADLINE_CONVS), ("vgg16", wl.VGG16_CONVS)):
+            for i, geom in enumerate(geoms):
+                c = ConvCase(geom, 8000 + i)
+                for _ in range(3):
+                    c.run()
+                us = timed_graph(c, 50 if c.M * c.N * c.K < 2e9 else 10) * 1e3
+                convs.append({"model": model, "H": geom[0], "W": geom[1], "Cin": geom[2], "Cout": geom[3], "kh": geom[4],
+                              "kw": geom[5], "stride": geom[6], "pad": geom[7], "M": c.M, "N": c.N, "K": c.K,
+                              "path": {1: "in place", 2: "im2row matrix"}[mg.conv2d_im2row_last_path()],
+                              "kernel": mg.gemm_kernel_name(mg.F32, mg.gemm_last_kernel_id()), "split": mg.gemm_last_split(),
+                              "us": round(us, 2), "tflops": round(2.0 * c.M * c.N * c.K / us / 1e6, 2),
+                              "gemm_us": gemm_us.get((c.M, c.N, c.K))})
+                del c
+            torch.cuda.empty_cache()
+        result["conv_im2row"] = convs
 
         # ---------------- solo mode: the micro-kernel of each data type's large-problem tile alone
         # (operands resident in LDS, pseudo-random values), the measured ceiling of that kernel here

@@ -53,3 +53,12 @@ def test_tables_follow_from_the_convolution_shapes():
               (28, 1, 512, 256), (14, 3, 256, 256), (14, 1, 256, 1024), (14, 1, 512, 1024), (14, 1, 1024, 256),
               (14, 1, 1024, 512), (7, 3, 512, 512), (7, 1, 512, 2048), (7, 1, 1024, 2048), (7, 1, 2048, 512)]
     assert [(hw * hw, cout, kk * kk * cin) for hw, kk, cin, cout in resnet] == list(wl.RESNET50_IM2ROW)
+
+
+def test_vgg16_layer_geometries_give_the_tables_gemm_sizes():
+    """m = Hout*Wout, n = Cout, k = kh*kw*Cin for every row (row 7: the table's n is a misprint, m and k agree)."""
+    assert len(wl.VGG16_CONVS) == len(wl.VGG16_IM2ROW)
+    for i, ((H, W, Cin, Cout, kh, kw, stride, pad), (m, n, k)) in enumerate(zip(wl.VGG16_CONVS, wl.VGG16_IM2ROW)):
+        Hout, Wout = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+        assert (Hout * Wout, kh * kw * Cin) == (m, k)
+        assert Cout == n or (i == 6 and (Cout, n) == (512, 256))

@@ -139,3 +139,12 @@ RESNET50_HEADLINE_CONVS = [
     (14, 14, 512, 512, 3, 3, 2, 1),
     (56, 56, 256, 64, 1, 1, 1, 0),
 ]
+
+# The 13 convolution layers of VGG16 (all 3 x 3, stride 1, padding 1) grouped as in the paper's Table
+# "vgg16" (H, W, Cin, Cout, kh, kw, stride, pad), in the order of VGG16_IM2ROW.  Row 7 of the table prints
+# n = 256 where the network's layer has 512 output channels; the geometry keeps the network's value.
+VGG16_CONVS = [
+    (224, 224, 3, 64, 3, 3, 1, 1), (224, 224, 64, 64, 3, 3, 1, 1), (112, 112, 64, 128, 3, 3, 1, 1),
+    (112, 112, 128, 128, 3, 3, 1, 1), (56, 56, 128, 256, 3, 3, 1, 1), (56, 56, 256, 256, 3, 3, 1, 1),
+    (28, 28, 256, 512, 3, 3, 1, 1), (28, 28, 512, 512, 3, 3, 1, 1), (14, 14, 512, 512, 3, 3, 1, 1),
+]
