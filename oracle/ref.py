@@ -53,6 +53,9 @@ def _load():
         lib.ref_bfloat16_to_double.restype = dbl
         lib.ref_bfloat16_to_double.argtypes = [ctypes.c_uint16]
         lib.ref_num_threads.restype = ctypes.c_int
+        for name in ("ref_narrow_f16", "ref_narrow_bf16"):
+            getattr(lib, name).restype = None
+            getattr(lib, name).argtypes = [vp, vp, i64]
         lib.ref_im2row_f32.restype = ctypes.c_int
         lib.ref_im2row_f32.argtypes = [i64] * 10 + [vp, vp]
         lib.ref_conv2d_nhwc_f32.restype = ctypes.c_int
@@ -211,6 +214,33 @@ def conv2d_nhwc_f32(x, w, stride, pad, alpha=1.0, beta=0.0, y_old=None):
     if rc != 0:
         raise RuntimeError("oracle returned %d" % rc)
     return out
+
+
+def narrow_f16(d):
+    """float64 array -> IEEE binary16 bit patterns (uint16), one rounding to nearest even."""
+    d = np.ascontiguousarray(d, dtype=np.float64)
+    out = np.zeros(d.shape, dtype=np.uint16)
+    _load().ref_narrow_f16(_ptr(d), _ptr(out), d.size)
+    return out
+
+
+def narrow_bf16(d):
+    """float64 array -> bfloat16 bit patterns (uint16), one rounding to nearest even."""
+    d = np.ascontiguousarray(d, dtype=np.float64)
+    out = np.zeros(d.shape, dtype=np.uint16)
+    _load().ref_narrow_bf16(_ptr(d), _ptr(out), d.size)
+    return out
+
+
+def half_bits_to_double(bits):
+    """uint16 array of binary16 patterns -> float64 (numpy's float16 is IEEE binary16; pinned against ref_half_to_double)."""
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def bfloat16_bits_to_double(bits):
+    """uint16 array of bfloat16 patterns -> float64: the pattern is the upper half of an fp32."""
+    with np.errstate(invalid="ignore"):      # signalling NaN patterns
+        return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
 def wrap_int32(d):

@@ -287,3 +287,46 @@ int ref_gemm_sample(int dtype, int layout, int64_t K,
     }
     return 0;
 }
+
+/*
+ * Narrowing of a wide result to a 16-bit storage format, for the entry points that keep C in 16 bits
+ * (paper Sec. "Data types": the type of the operands of a micro-kernel is a parameter).  One rounding
+ * to nearest, ties to even, of the value given; overflow gives infinity, NaN stays NaN (quiet).
+ * frac_bits = 10, min_exp = -14, max_exp = 15 is IEEE binary16; 7, -126, 127 is bfloat16.
+ * The scaling by a power of two and nearbyint() (default rounding mode: to nearest even) are exact
+ * steps, so this is the definition written out.  Pinned against numpy's float16 conversion, against
+ * round trips of all 65536 patterns of both formats and against hand-picked ties.
+ */
+static uint16_t narrow16(double x, int frac_bits, int min_exp, int max_exp)
+{
+    const int exp_bits = 15 - frac_bits;
+    const uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    const uint16_t exp_all = (uint16_t)(((1u << exp_bits) - 1u) << frac_bits);
+    if (isnan(x)) return (uint16_t)(sign | exp_all | (1u << (frac_bits - 1)));
+    const double a = fabs(x);
+    if (isinf(a)) return (uint16_t)(sign | exp_all);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                       /* a in [2^(e-1), 2^e) */
+    int exp = e - 1;
+    if (exp < min_exp) exp = min_exp;         /* subnormal range: fixed quantum */
+    const double quantum = ldexp(1.0, exp - frac_bits);
+    const double r = nearbyint(a / quantum) * quantum;
+    const double largest = (2.0 - ldexp(1.0, -frac_bits)) * ldexp(1.0, max_exp);
+    if (r > largest) return (uint16_t)(sign | exp_all);
+    if (r < ldexp(1.0, min_exp)) return (uint16_t)(sign | (uint16_t)(r / ldexp(1.0, min_exp - frac_bits)));
+    (void)frexp(r, &e);
+    exp = e - 1;
+    const double frac = r / ldexp(1.0, exp) - 1.0;
+    return (uint16_t)(sign | (uint16_t)((exp - min_exp + 1) << frac_bits) | (uint16_t)(frac * (double)(1 << frac_bits)));
+}
+
+void ref_narrow_f16(const double *x, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = narrow16(x[i], 10, -14, 15);
+}
+
+void ref_narrow_bf16(const double *x, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = narrow16(x[i], 7, -126, 127);
+}

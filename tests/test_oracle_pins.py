@@ -563,3 +563,54 @@ def test_conv_is_the_gemm_of_the_im2row_matrix_and_matches_torch():
         if kh == 1 and kw == 1:
             # a 1 x 1 filter at stride 1 is the plain GEMM of the image with the filter
             assert np.array_equal(A, x.reshape(M, K))
+
+
+# ------------------------------------------------------------ narrowing to 16-bit storage
+def test_narrowing_to_binary16_against_numpy_and_by_hand():
+    # every pattern survives the round trip (NaNs stay NaN)
+    bits = np.arange(65536, dtype=np.uint16)
+    vals = oracle.half_bits_to_double(bits)
+    back = oracle.narrow_f16(vals)
+    finite = ~np.isnan(vals)
+    assert np.array_equal(back[finite], bits[finite])
+    assert np.all(np.isnan(oracle.half_bits_to_double(back[~finite])))
+    for b in (0x0001, 0x03FF, 0x0400, 0x3C00, 0x7BFF, 0xFBFF, 0x8000):
+        assert oracle.half_to_double(b) == vals[b]
+    # ties go to the even neighbour; just above a tie goes up (ulp(1) = 2^-10)
+    cases = {1 + 2.0 ** -11: 0x3C00, 1 + 2.0 ** -11 + 2.0 ** -30: 0x3C01, 1 + 3 * 2.0 ** -11: 0x3C02,
+             65504.0: 0x7BFF, 65519.999: 0x7BFF, 65520.0: 0x7C00, -65520.0: 0xFC00, 1e9: 0x7C00,
+             2.0 ** -24: 0x0001, 2.0 ** -25: 0x0000, 2.0 ** -25 * 1.0001: 0x0001, 3 * 2.0 ** -25: 0x0002,
+             2.0 ** -14 - 2.0 ** -25: 0x0400, -0.0: 0x8000, float("inf"): 0x7C00}
+    for x, want in cases.items():
+        assert int(oracle.narrow_f16(np.array([x]))[0]) == want, (x, hex(want))
+    # against numpy's conversion on values of every magnitude, and on every midpoint between neighbours
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(200000) * np.exp(rng.uniform(-20, 12, 200000))
+    with np.errstate(over="ignore"):
+        assert np.array_equal(oracle.narrow_f16(x), x.astype(np.float16).view(np.uint16))
+        pos = oracle.half_bits_to_double(np.arange(0, 0x7BFF, dtype=np.uint16))
+        mid = (pos[:-1] + pos[1:]) / 2
+        assert np.array_equal(oracle.narrow_f16(mid), mid.astype(np.float16).view(np.uint16))
+        assert np.array_equal(oracle.narrow_f16(mid) & 1, np.zeros(mid.size, dtype=np.uint16))
+
+
+def test_narrowing_to_bfloat16():
+    bits = np.arange(65536, dtype=np.uint16)
+    vals = oracle.bfloat16_bits_to_double(bits)
+    back = oracle.narrow_bf16(vals)
+    finite = ~np.isnan(vals)
+    assert np.array_equal(back[finite], bits[finite])
+    for b in (0x0001, 0x007F, 0x0080, 0x3F80, 0x7F7F, 0xFF7F):
+        assert oracle.bfloat16_to_double(b) == vals[b]
+    # ulp(1) = 2^-7: ties to even, just above goes up, overflow, smallest subnormal 2^-133
+    cases = {1 + 2.0 ** -8: 0x3F80, 1 + 2.0 ** -8 + 2.0 ** -40: 0x3F81, 1 + 3 * 2.0 ** -8: 0x3F82,
+             (2 - 2.0 ** -7) * 2.0 ** 127: 0x7F7F, (2 - 2.0 ** -8) * 2.0 ** 127: 0x7F80, 2.0 ** -133: 0x0001,
+             2.0 ** -134: 0x0000, -1.0: 0xBF80}
+    for x, want in cases.items():
+        assert int(oracle.narrow_bf16(np.array([x]))[0]) == want, (x, hex(want))
+    # on fp32 values the integer rule "add 0x7FFF plus the lowest kept bit, cut" is the same rounding
+    rng = np.random.default_rng(6)
+    f = (rng.standard_normal(200000) * np.exp(rng.uniform(-60, 60, 200000))).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    want = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(oracle.narrow_bf16(f.astype(np.float64)), want)
