@@ -79,14 +79,16 @@ def main():
         return t.cuda()
 
     fn = {"f32": mg.gemm_f32, "f16": mg.gemm_f16, "i8": mg.gemm_i8, "bf16": mg.gemm_bf16}
+    fn_c16 = {"f16": mg.gemm_f16_c16, "bf16": mg.gemm_bf16_c16}
     code = {"f32": mg.F32, "f16": mg.F16, "i8": mg.I8, "bf16": mg.BF16}
     lay = {"col": mg.COL_MAJOR, "row": mg.ROW_MAJOR}
 
     class Case:
         """One GEMM with its operands on the device."""
 
-        def __init__(self, dtype, layout, M, N, K, alpha, beta, seed, trans=(0, 0)):
+        def __init__(self, dtype, layout, M, N, K, alpha, beta, seed, trans=(0, 0), c16=False):
             self.dtype, self.layout, self.M, self.N, self.K = dtype, layout, M, N, K
+            self.c16 = c16              # C kept in the 16-bit format of the inputs
             self.trans = trans          # square problems only: the stored shapes do not change
             self.lda, self.ldb, self.ldc = wl.tight_ld(layout, M, K), wl.tight_ld(layout, K, N), wl.tight_ld(layout, M, N)
             if dtype == "f32":
@@ -96,7 +98,7 @@ def main():
             elif dtype in ("f16", "bf16"):
                 gen = wl.normal_f16_bits if dtype == "f16" else wl.normal_bf16_bits
                 A, B = gen(seed, layout, M, K), gen(seed + 1, layout, K, N)
-                C = np.zeros(wl._shape(layout, M, N, self.ldc), dtype=np.float32)
+                C = np.zeros(wl._shape(layout, M, N, self.ldc), dtype=np.uint16 if c16 else np.float32)
                 self.alpha, self.beta = float(alpha), float(beta)
             else:
                 A, B = wl.uniform_i8(seed, layout, M, K), wl.uniform_i8(seed + 1, layout, K, N)
@@ -113,8 +115,8 @@ def main():
                 mg.gemm_ex(code[self.dtype], lay[self.layout], self.trans[0], self.trans[1], self.M, self.N, self.K,
                            self.alpha, self.A, self.lda, self.B, self.ldb, self.beta, self.C, self.ldc, self.ws, on)
                 return
-            fn[self.dtype](lay[self.layout], self.M, self.N, self.K, self.alpha, self.A, self.lda, self.B, self.ldb,
-                           self.beta, self.C, self.ldc, self.ws, on)
+            (fn_c16 if self.c16 else fn)[self.dtype](lay[self.layout], self.M, self.N, self.K, self.alpha, self.A, self.lda,
+                                                     self.B, self.ldb, self.beta, self.C, self.ldc, self.ws, on)
 
         def kernel(self):
             self.run()
@@ -241,6 +243,8 @@ def main():
                    "K": case.K, "kernel": name, "split": split}
             if case.trans != (0, 0):
                 row["transa"], row["transb"] = case.trans
+            if case.c16:
+                row["c_storage"] = case.dtype
             if best < 0.1:
                 # short GEMMs: back-to-back eager launches are bounded by the host's launch rate, so the
                 # figure of merit is the replay of a captured graph; the eager figure is kept beside it
@@ -262,6 +266,9 @@ def main():
             torch.cuda.empty_cache()
         for i, n in enumerate(wl.FP16_SQUARES[1:]):
             measure("bf16 square (beyond the configurations)", Case("bf16", "row", n, n, n, 1.0, 0.0, 3500 + i))
+            torch.cuda.empty_cache()
+        for dt16 in ("f16", "bf16"):
+            measure("C kept in 16 bits (beyond the configurations)", Case(dt16, "row", 8192, 8192, 8192, 1.0, 0.0, 3550, c16=True))
             torch.cuda.empty_cache()
         for trans in ((1, 0), (0, 1), (1, 1)):
             measure("transposed operands (beyond the configurations)",

@@ -88,6 +88,22 @@ int gemm_bf16(int layout, int64_t M, int64_t N, int64_t K,
               float beta, float *C, int64_t ldc,
               void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same two with C kept in the 16-bit format of the inputs (bit patterns), in and out: the product
+ * is accumulated in fp32, alpha*acc + beta*C_old is evaluated in fp32 and rounded once, to nearest
+ * even, when it is stored (overflow gives infinity).  The storage type of C is one more of the
+ * type parameters the paper's Sec. "Data types" changes.  ldc counts 16-bit elements; the K-split
+ * workspace still holds fp32 partial tiles.  Everything else as gemm_f16 / gemm_bf16. */
+int gemm_f16_c16(int layout, int64_t M, int64_t N, int64_t K,
+                 float alpha, const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb,
+                 float beta, uint16_t *C, int64_t ldc,
+                 void *workspace, size_t workspace_bytes, void *stream);
+int gemm_bf16_c16(int layout, int64_t M, int64_t N, int64_t K,
+                  float alpha, const uint16_t *A, int64_t lda,
+                  const uint16_t *B, int64_t ldb,
+                  float beta, uint16_t *C, int64_t ldc,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* int8 inputs, int32 accumulation, int32 C in and out, int32 alpha and beta.
  * The result is exact (bit-for-bit) as long as the true value of every
  * intermediate fits in int32, which holds for K <= 131071 at alpha = 1,

@@ -39,7 +39,7 @@ def load():
     lib = ctypes.CDLL(_LIB_PATH)
     i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     for name, scal in (("gemm_f32", ctypes.c_float), ("gemm_f16", ctypes.c_float), ("gemm_bf16", ctypes.c_float),
-                       ("gemm_i8", ctypes.c_int32)):
+                       ("gemm_f16_c16", ctypes.c_float), ("gemm_bf16_c16", ctypes.c_float), ("gemm_i8", ctypes.c_int32)):
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [ci, i64, i64, i64, scal, vp, i64, vp, i64, scal, vp, i64, vp, sz, vp]
@@ -206,6 +206,14 @@ def gemm_last_kernel_id():
 
 def gemm_last_split():
     return int(load().gemm_last_split())
+
+
+def gemm_f16_c16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    return _call("gemm_f16_c16", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def gemm_bf16_c16(layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    return _call("gemm_bf16_c16", layout, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
 
 
 def conv2d_im2row_f32(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, alpha, image, filter, beta, output,

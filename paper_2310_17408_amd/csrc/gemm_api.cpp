@@ -180,7 +180,8 @@ bool aligned16(const void *p, int64_t ld, int es)
 // transa / transb: op(A) = A^T / op(B) = B^T (gemm_ex only; checked by the caller).
 int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t alpha_bits, bool alpha_zero,
         const void *A, int64_t lda, const void *B, int64_t ldb, uint32_t beta_bits, bool beta_zero, bool beta_one,
-        void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream_, bool transa = false, bool transb = false)
+        void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream_, bool transa = false, bool transb = false,
+        int c_type = C_WIDE)
 {
     t_last_id = -1;
     t_last_split = 0;
@@ -221,7 +222,7 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
 
     if (no_product) {
         if (beta_one) return 0;
-        hipError_t e = launch_scale(dtype, C, (int)Mc, (int)Nc, ldc, beta_bits, beta_zero ? 0 : 1, stream);
+        hipError_t e = launch_scale(dtype, C, (int)Mc, (int)Nc, ldc, beta_bits, beta_zero ? 0 : 1, stream, c_type);
         return e == hipSuccess ? 0 : (int)e;
     }
 
@@ -249,11 +250,12 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     p.b_nc = b_nc ? 1 : 0;
     p.group_m = 8;
     p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
+    p.c_type = c_type;
 
     hipError_t e = ki->launch(p, stream);
     if (e != hipSuccess) return (int)e;
     if (p.split > 1) {
-        e = launch_reduce(dtype, ws, C, p.M, p.N, ldc, p.split, alpha_bits, beta_bits, p.use_beta, stream);
+        e = launch_reduce(dtype, ws, C, p.M, p.N, ldc, p.split, alpha_bits, beta_bits, p.use_beta, stream, c_type);
         if (e != hipSuccess) return (int)e;
     }
     t_last_id = ch.id;
@@ -358,6 +360,22 @@ int gemm_bf16(int layout, int64_t M, int64_t N, int64_t K, float alpha, const ui
 {
     return run(MI_GEMM_BF16, 2, layout, M, N, K, bits_of(alpha), alpha == 0.0f, A, lda, B, ldb, bits_of(beta),
                beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream);
+}
+
+int gemm_f16_c16(int layout, int64_t M, int64_t N, int64_t K, float alpha, const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb, float beta, uint16_t *C, int64_t ldc, void *workspace,
+                 size_t workspace_bytes, void *stream)
+{
+    return run(MI_GEMM_F16, 2, layout, M, N, K, bits_of(alpha), alpha == 0.0f, A, lda, B, ldb, bits_of(beta),
+               beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream, false, false, C_F16);
+}
+
+int gemm_bf16_c16(int layout, int64_t M, int64_t N, int64_t K, float alpha, const uint16_t *A, int64_t lda,
+                  const uint16_t *B, int64_t ldb, float beta, uint16_t *C, int64_t ldc, void *workspace,
+                  size_t workspace_bytes, void *stream)
+{
+    return run(MI_GEMM_BF16, 2, layout, M, N, K, bits_of(alpha), alpha == 0.0f, A, lda, B, ldb, bits_of(beta),
+               beta == 0.0f, beta == 1.0f, C, ldc, workspace, workspace_bytes, stream, false, false, C_BF16);
 }
 
 int gemm_i8(int layout, int64_t M, int64_t N, int64_t K, int32_t alpha, const int8_t *A, int64_t lda, const int8_t *B,

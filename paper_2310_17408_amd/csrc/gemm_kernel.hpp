@@ -197,6 +197,39 @@ __device__ __forceinline__ void tile_coords(const Params &p, int bid, int &tm, i
     tn = (pid % group) / gm;
 }
 
+// C kept in 16 bits (binary16 or bfloat16; paper Sec. "Data types": the storage type of an operand is a
+// parameter of the micro-kernel): the update is evaluated in fp32 and rounded once, to nearest even.
+__device__ __forceinline__ float narrow_load(int c_type, const void *C, int64_t idx)
+{
+    const uint16_t b = ((const uint16_t *)C)[idx];
+    if (c_type == C_F16) return (float)__builtin_bit_cast(_Float16, b);
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+__device__ __forceinline__ void narrow_store(int c_type, void *C, int64_t idx, float v)
+{
+    uint16_t b;
+    if (c_type == C_F16) {
+        b = __builtin_bit_cast(uint16_t, (_Float16)v);
+    } else {
+        const uint32_t u = __builtin_bit_cast(uint32_t, v);
+        b = (v != v) ? (uint16_t)((u >> 16) | 0x40u) : (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    }
+    ((uint16_t *)C)[idx] = b;
+}
+// C(idx) <- alpha*a + beta*C(idx) for a float accumulator, C stored as p.c_type says
+__device__ __forceinline__ void update_c(const Params &p, int64_t idx, float a, float alpha, float beta, bool use_beta)
+{
+    float o = alpha * a;
+    if (p.c_type == C_WIDE) {
+        float *c = (float *)p.C + idx;
+        if (use_beta) o += beta * (*c);
+        *c = o;
+    } else {
+        if (use_beta) o += beta * narrow_load(p.c_type, p.C, idx);
+        narrow_store(p.c_type, p.C, idx, o);
+    }
+}
+
 // Epilogue: C <- alpha*acc + beta*C, or the raw partial tile into the workspace
 // when K is split.  In every 32 x 32 block a lane holds one row m and the 16
 // columns n = 8*(v/4) + 4*(lane/32) + v%4, so the 32 lanes of a half-wave write
@@ -232,6 +265,8 @@ __device__ __forceinline__ void store_tile(typename DT::accv (&acc)[TM][TN], con
                             uint32_t r = (uint32_t)alpha * (uint32_t)a;
                             if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
                             *c = (int)r;
+                        } else if constexpr (DT::ES == 2) {
+                            update_c(p, (int64_t)n * p.ldc + m, a, alpha, beta, use_beta);
                         } else {
                             float r = alpha * a;
                             if (use_beta) r += beta * (*c);
@@ -488,7 +523,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 template <class acc_t>
 __global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ ws, acc_t *__restrict__ C, int M, int N,
                                                      int64_t ldc, int split, uint32_t alpha_bits, uint32_t beta_bits,
-                                                     int use_beta)
+                                                     int use_beta, int c_type)
 {
     const int64_t total = (int64_t)M * N;
     const acc_t alpha = __builtin_bit_cast(acc_t, alpha_bits);
@@ -526,8 +561,13 @@ __global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ w
             }
             for (; zz < split; ++zz) s += src[(int64_t)zz * total];
             acc_t r = alpha * s;
-            if (use_beta) r += beta * (*c);
-            *c = r;
+            if (c_type == C_WIDE) {
+                if (use_beta) r += beta * (*c);
+                *c = r;
+            } else {
+                if (use_beta) r += beta * narrow_load(c_type, C, n * ldc + m);
+                narrow_store(c_type, C, n * ldc + m, r);
+            }
         }
     }
 }
@@ -559,7 +599,7 @@ __global__ void __launch_bounds__(256) im2row_matrix_kernel(const float *__restr
 // C <- beta*C (K == 0 or alpha == 0); beta == 0 stores zeros without reading C.
 template <class acc_t>
 __global__ void __launch_bounds__(256) scale_kernel(acc_t *__restrict__ C, int M, int N, int64_t ldc,
-                                                    uint32_t beta_bits, int use_beta)
+                                                    uint32_t beta_bits, int use_beta, int c_type)
 {
     const int64_t total = (int64_t)M * N;
     const acc_t beta = __builtin_bit_cast(acc_t, beta_bits);
@@ -568,6 +608,12 @@ __global__ void __launch_bounds__(256) scale_kernel(acc_t *__restrict__ C, int M
         const int m = (int)(idx % M);
         const int64_t n = idx / M;
         acc_t *c = C + n * ldc + m;
+        if constexpr (!__is_same(acc_t, int)) {
+            if (c_type != C_WIDE) {
+                narrow_store(c_type, C, n * ldc + m, use_beta ? beta * narrow_load(c_type, C, n * ldc + m) : 0.0f);
+                continue;
+            }
+        }
         if (use_beta) {
             if constexpr (__is_same(acc_t, int)) *c = (int)((uint32_t)beta * (uint32_t)(*c));
             else *c = beta * (*c);

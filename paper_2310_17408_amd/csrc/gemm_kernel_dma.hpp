@@ -301,9 +301,7 @@ struct DmaMicro16 {
                                 if (use_beta) o += (uint32_t)beta * (uint32_t)(*c);
                                 *c = (int)o;
                             } else {
-                                float o = alpha * a;
-                                if (use_beta) o += beta * (*c);
-                                *c = o;
+                                update_c(p, (int64_t)n * p.ldc + m, a, alpha, beta, use_beta);
                             }
                         }
                     }

@@ -401,9 +401,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg16(const Params
                             if (use_beta) o += (uint32_t)beta * (uint32_t)(*c);
                             *c = (int)o;
                         } else {
-                            float o = alpha * a;
-                            if (use_beta) o += beta * (*c);
-                            *c = o;
+                            update_c(p, (int64_t)n * p.ldc + m, a, alpha, beta, use_beta);
                         }
                     }
                 }

@@ -34,7 +34,9 @@ struct Params {
     int group_m;           // tiles per column group in the tile order
     int xcd_remap;         // deal contiguous tile ranges to the 8 XCDs
     Im2row conv;           // implicit-im2row launches only: B is the image, ldb is unused
+    int c_type;            // how C is stored: C_WIDE as the accumulators (fp32 / int32), C_F16, C_BF16 (16-bit inputs only)
 };
+enum { C_WIDE = 0, C_F16 = 1, C_BF16 = 2 };
 
 struct KernelInfo {
     const char *name;
@@ -75,11 +77,11 @@ int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 i
 const KernelInfo *kernel_info(int dtype, int id);  // nullptr if out of range
 
 hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
-                         uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream);
+                         uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream, int c_type = C_WIDE);
 // The im2row matrix [rows][K] (row-major, K = kh*kw*Cin, kh given by K) of a channels-last fp32 image.
 hipError_t launch_im2row_matrix(const float *image, float *matrix, int64_t rows, int64_t K, const Im2row &g,
                                 hipStream_t stream);
 hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
-                        hipStream_t stream);
+                        hipStream_t stream, int c_type = C_WIDE);
 
 }  // namespace mig

@@ -283,15 +283,15 @@ static unsigned blocks_for(int64_t total)
 }
 
 hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
-                         uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream)
+                         uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream, int c_type)
 {
     const unsigned g = blocks_for((int64_t)M * N);
     if (dtype == 2)
         hipLaunchKernelGGL(reduce_kernel<int>, dim3(g), dim3(256), 0, stream, (const int *)ws, (int *)C, M, N, ldc,
-                           split, alpha_bits, beta_bits, use_beta);
+                           split, alpha_bits, beta_bits, use_beta, C_WIDE);
     else
         hipLaunchKernelGGL(reduce_kernel<float>, dim3(g), dim3(256), 0, stream, (const float *)ws, (float *)C, M, N,
-                           ldc, split, alpha_bits, beta_bits, use_beta);
+                           ldc, split, alpha_bits, beta_bits, use_beta, c_type);
     return hipGetLastError();
 }
 
@@ -303,14 +303,14 @@ hipError_t launch_im2row_matrix(const float *image, float *matrix, int64_t rows,
 }
 
 hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
-                        hipStream_t stream)
+                        hipStream_t stream, int c_type)
 {
     const unsigned g = blocks_for((int64_t)M * N);
     if (dtype == 2)
-        hipLaunchKernelGGL(scale_kernel<int>, dim3(g), dim3(256), 0, stream, (int *)C, M, N, ldc, beta_bits, use_beta);
+        hipLaunchKernelGGL(scale_kernel<int>, dim3(g), dim3(256), 0, stream, (int *)C, M, N, ldc, beta_bits, use_beta, C_WIDE);
     else
         hipLaunchKernelGGL(scale_kernel<float>, dim3(g), dim3(256), 0, stream, (float *)C, M, N, ldc, beta_bits,
-                           use_beta);
+                           use_beta, c_type);
     return hipGetLastError();
 }
 
