@@ -41,7 +41,7 @@ def test_kernel_table():
     assert mg.gemm_force_kernel(5, 0, 0) == -1
 
 
-@pytest.mark.parametrize("fn", [mg.gemm_f32, mg.gemm_f16, mg.gemm_i8, mg.gemm_bf16])
+@pytest.mark.parametrize("fn", [mg.gemm_f32, mg.gemm_f16, mg.gemm_i8, mg.gemm_bf16, mg.gemm_f16_c16, mg.gemm_bf16_c16])
 def test_argument_errors_return_before_any_launch(fn):
     P = 0x1000            # never dereferenced: every call below fails validation or returns early
     ok = dict(layout=mg.COL_MAJOR, M=8, N=9, K=10, alpha=1, A=P, lda=8, B=P, ldb=10, beta=0, C=P, ldc=8)
