@@ -52,16 +52,28 @@ struct DmaTile {
     // transposing read: a group of 16 lanes reads KH k-rows x 16 m; LPR lanes share a row
     static constexpr int LPR = 2 * ES;                  // 4 (16-bit) or 2 (8-bit)
     static constexpr int KH = 16 / LPR;                 // k-rows per transposing read: 4 or 8
-    // A chunk swizzle: chunk ^ ((k & SWZ_MASK) << SWZ_SHIFT) spreads KH consecutive k-rows
+    // A chunk swizzle: the chunk index of k-row k is XORed with a_swz(k), so that one pass of the
+    // transposing reads (32 lanes: KH consecutive k-rows of two neighbouring k groups, LPR 8-byte pieces
+    // each) touches every LDS bank once.  With k-rows of 256 bytes or more the KH rows take the upper
+    // chunk bits and the parity of the k group the bit below them; with 128-byte k-rows (int8, BM = 128)
+    // the parity of k is an address bit already and the row pairs take the swizzle.
     static constexpr int SWZ_SHIFT = (ES == 2) ? 2 : 1;
     static constexpr int SWZ_MASK_FULL = KH - 1;
     static constexpr int SWZ_MASK = ((SWZ_MASK_FULL << SWZ_SHIFT) < A_CPR) ? SWZ_MASK_FULL : (SWZ_MASK_FULL >> 1);
+    static constexpr int SWZ_PERIOD = 2 * KCH;          // a_swz(k + SWZ_PERIOD) == a_swz(k)
+    static __host__ __device__ constexpr int a_swz(int k)
+    {
+        return A_CPR >= 16 ? (((k & SWZ_MASK_FULL) << SWZ_SHIFT) ^ (((k / KCH) & 1) << (SWZ_SHIFT - 1)))
+                           : ((((k >> 1) & 3) << 1) ^ ((k / KCH) & 1));
+    }
     static_assert(KSTEPS == 2 || KSTEPS == 4, "a B row holds 4 or 8 chunks");
     static_assert(NSTAGE >= 2 && (NSTAGE - 2) * INST <= 63, "transfers in flight must fit the counter");
     static_assert(ES == 1 || ES == 2, "transposing LDS reads exist for 8- and 16-bit elements");
     static_assert(A_ROWB <= 1024 && 1024 % A_ROWB == 0, "a 1 KiB transfer must cover whole k-rows of A");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tiles must split evenly over the waves");
-    static_assert((SWZ_MASK << SWZ_SHIFT) < A_CPR, "swizzle must stay inside a row");
+    static_assert(A_CPR >= 16 || (A_CPR == 8 && ES == 1), "k-rows of at least 256 bytes, or 128 bytes of int8");
+    static_assert(A_CPR >= 16 ? ((SWZ_MASK_FULL << SWZ_SHIFT) | (1 << (SWZ_SHIFT - 1))) < A_CPR : true,
+                  "swizzle must stay inside a row");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tiles are made of 32x32 blocks");
 };
 
@@ -146,7 +158,7 @@ struct DmaMicro {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int mbyte = (wm0 + 32 * i + 16 * mh) * ES + 8 * ml;
-            const int ch = (mbyte >> 4) ^ ((kr & T::SWZ_MASK) << T::SWZ_SHIFT);
+            const int ch = (mbyte >> 4) ^ T::a_swz(KCH * fgrp + kr);
             aoff[i] = (KCH * fgrp + kr) * A_ROWB + (ch << 4) + (mbyte & 15);
         }
     }
@@ -246,7 +258,7 @@ struct DmaMicro16 {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int mbyte = (wm0 + 16 * i) * ES + 8 * ml;
-            const int ch = (mbyte >> 4) ^ ((kr & T::SWZ_MASK) << T::SWZ_SHIFT);
+            const int ch = (mbyte >> 4) ^ T::a_swz(KCH * g + kr);
             aoff[i] = (KCH * g + kr) * A_ROWB + (ch << 4) + (mbyte & 15);
         }
     }
@@ -356,9 +368,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     const int b_row_in = lane / T::B_CPR, b_pch = lane % T::B_CPR;
     // The swizzle term of a lane's row does not depend on j (NW transfers apart the row pattern
     // repeats), so a lane's byte offset from the block's first element is the same in every transfer.
-    static_assert((NW * T::A_ROWS_PER_INST) % (T::SWZ_MASK + 1) == 0, "A swizzle must repeat every NW blocks");
+    static_assert((NW * T::A_ROWS_PER_INST) % T::SWZ_PERIOD == 0, "A swizzle must repeat every NW blocks");
     static_assert((NW * T::B_ROWS_PER_INST) % (T::B_RP256 * T::B_CPR) == 0, "B swizzle must repeat every NW blocks");
-    const int a_ch = a_pch ^ (((wave * T::A_ROWS_PER_INST + a_row_in) & T::SWZ_MASK) << T::SWZ_SHIFT);
+    const int a_ch = a_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + a_row_in);
     const int b_ch = b_pch ^ (((wave * T::B_ROWS_PER_INST + b_row_in) / T::B_RP256) % T::B_CPR);
     const uint32_t a_lane_off = (uint32_t)(((int64_t)a_row_in * p.lda + a_ch * (16 / ES)) * ES);
     const uint32_t b_lane_off = (uint32_t)(((int64_t)b_row_in * p.ldb + b_ch * KCH) * ES);
