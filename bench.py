@@ -376,6 +376,16 @@ def main():
             rate = solo_rate(dtype, names[dtype].index(big["kernel"]))
             ceilings[dtype] = {"kernel": big["kernel"], "solo_tflops": round(rate, 1),
                                "pct_peak": round(100.0 * rate / PEAK[dtype], 1)}
+        # the same MFMA shapes fed from registers only (the micro-kernel of the register-direct configuration with
+        # the largest wave tile): no LDS traffic either, so what is left below the peak is the clock the chip
+        # sustains under that instruction mix on random operands
+        for dtype in ("f32", "f16", "i8", "bf16"):
+            regs = [i for i, n in enumerate(names[dtype]) if n.endswith(("_reg", "_reg16")) and "_k" not in n]
+            if regs:
+                kid = max(regs, key=lambda i: mg.gemm_kernel_tile(code[dtype], i)[0] * mg.gemm_kernel_tile(code[dtype], i)[1])
+                rate = solo_rate(dtype, kid)
+                ceilings[dtype]["registers_only"] = {"kernel": names[dtype][kid], "solo_tflops": round(rate, 1),
+                                                     "pct_peak": round(100.0 * rate / PEAK[dtype], 1)}
         result["solo_mode"] = ceilings
         for r in rows:
             c = ceilings[r["dtype"]]
