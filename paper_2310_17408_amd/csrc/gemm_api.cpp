@@ -52,7 +52,7 @@ struct Choice { int id; int split; int ktiles_per_split; };
 // partial-tile round trip, 2.5 us per launch, 3.0 us for the second launch.
 // ---------------------------------------------------------------------------
 constexpr double kSustainedTflops[NUM_DTYPES] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61, 2516.6 * 0.58};
-constexpr double kStagingBytesPerUs = 14.0e6;
+constexpr double kStagingBytesPerUs = 17.0e6;
 constexpr double kStepFloorUs = 0.75;
 constexpr double kGuardedStepFactor = 2.2;
 constexpr double kReduceBytesPerUs = 4.0e6;
