@@ -48,7 +48,7 @@ struct Choice { int id; int split; int ktiles_per_split; };
 //     rounds  = waves / (SIMDs * waves per SIMD), at least 1
 // reduce = second launch + split partial tiles written and read back.
 // The constants are measured on MI355X with HIP-graph replays: sustained MFMA rate per data type
-// (solo mode on random data), 14 TB/s from L2 into LDS for GEMM-like tile streams, 4 TB/s for the
+// (solo mode on random data), 17 TB/s from L2 into LDS for GEMM-like tile streams, 4 TB/s for the
 // partial-tile round trip, 2.5 us per launch, 3.0 us for the second launch.
 // ---------------------------------------------------------------------------
 constexpr double kSustainedTflops[NUM_DTYPES] = {157.3 * 0.97, 2516.6 * 0.58, 5033.2 * 0.61, 2516.6 * 0.58};
