@@ -279,6 +279,7 @@ thread_local int t_conv_path = 0;
 int g_conv_forced_path = 0;
 // forming the matrix, measured: about 5 us plus its bytes at 1.35 TB/s (a launch, one element per thread)
 constexpr double kIm2rowFixedUs = 5.0, kIm2rowBytesPerUs = 1.35e6;
+constexpr double kIm2rowLdsFactor = 1.4, kIm2rowRegFactor = 1.08;
 
 // 0, or -k for the k-th argument of conv2d_im2row_f32 (Cout is not checked when it is 0: im2row_f32)
 int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw, int64_t stride_h,
@@ -311,22 +312,41 @@ int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout
 bool conv_fused_ok(int64_t batch, const ConvGeometry &c)
 {
     const unsigned __int128 image_bytes = (unsigned __int128)batch * c.g.H * c.g.W * (unsigned __int128)c.g.Cin * 4u;
-    return image_bytes < ((unsigned __int128)1 << 31) && (c.g.Cin % 16 == 0 || c.K < ((int64_t)1 << 22));
+    return image_bytes < ((unsigned __int128)1 << 31);
+}
+
+// How configuration ki can read the im2row matrix in place: a K step inside one filter tap (Cin a multiple
+// of its K step; the direct-to-LDS kernels also need a 16-byte aligned image), element by element along
+// filter rows (register-direct kernels, K below 2^22), or not at all.
+typedef hipError_t (*LaunchFn)(const Params &, hipStream_t);
+LaunchFn conv_fused_launcher(const KernelInfo *ki, const ConvGeometry &c, bool image_aligned)
+{
+    const bool lds_kernel = ki->waves_k == 0;
+    if (ki->launch_im2row && c.g.Cin % ki->BK == 0 && (!lds_kernel || image_aligned)) return ki->launch_im2row;
+    if (ki->launch_im2row_runs && c.K < ((int64_t)1 << 22)) return ki->launch_im2row_runs;
+    return nullptr;
 }
 
 // Best fused configuration (canonical problem N x M x K) for a workspace that holds `fit` partial tiles;
 // -1 if none.
-int conv_fused_kernel(const ConvGeometry &c, int64_t fit, double *us)
+int conv_fused_kernel(const ConvGeometry &c, int64_t fit, bool image_aligned, double *us)
 {
     int best = -1;
     double best_us = 0.0;
     const Forced f = g_forced[MI_GEMM_F32];
     for (int id = 0; id < kernel_count(MI_GEMM_F32); ++id) {
         const KernelInfo *ki = kernel_info(MI_GEMM_F32, id);
-        if (!ki->launch_im2row || !can_address(ki, c.N, 0)) continue;
+        if (!conv_fused_launcher(ki, c, image_aligned) || !can_address(ki, c.N, 0)) continue;
         if (f.id >= 0 ? id != f.id : ki->prio <= 0) continue;
-        const int s = auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit);
-        const double t = predict_us(MI_GEMM_F32, ki, c.N, c.M, c.K, s);
+        int s = auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit);
+        // a direct-to-LDS kernel that would need its K split (few tiles, every step latency-bound) loses to
+        // the register-direct kernels in every layer measured: it competes unsplit only
+        if (ki->waves_k == 0 && f.split < 1) s = 1;
+        double t = predict_us(MI_GEMM_F32, ki, c.N, c.M, c.K, s);
+        // measured against the GEMM on a matrix that exists: the direct-to-LDS kernels pay for the clamped
+        // addresses and the zeroing between the wait and the barrier of every K step, the register-direct
+        // ones for the masks of their loads
+        t = kLaunchUs + (t - kLaunchUs) * (ki->waves_k == 0 ? kIm2rowLdsFactor : kIm2rowRegFactor);
         if (best < 0 || t < best_us) { best = id; best_us = t; }
     }
     if (us) *us = best_us;
@@ -563,7 +583,8 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
     if (fit > MAX_SPLIT) fit = MAX_SPLIT;
     if (fit < 1) fit = 1;
     double fused_us = 0.0;
-    const int fused_id = conv_fused_ok(batch, c) ? conv_fused_kernel(c, fit, &fused_us) : -1;
+    const bool image_aligned = (uintptr_t)image % 16 == 0;
+    const int fused_id = conv_fused_ok(batch, c) ? conv_fused_kernel(c, fit, image_aligned, &fused_us) : -1;
     // explicit: the matrix in the workspace, then the GEMM with what is left of it
     const bool explicit_fits = ws_bytes >= matrix_bytes;
     bool fused = fused_id >= 0;
@@ -591,7 +612,7 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
     const KernelInfo *ki = kernel_info(MI_GEMM_F32, fused_id);
     const Forced f = g_forced[MI_GEMM_F32];
     const int64_t ktiles = ceil_div(c.K, ki->BK);
-    int64_t sp = f.split >= 1 ? f.split : auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit);
+    int64_t sp = f.split >= 1 ? f.split : (ki->waves_k == 0 ? 1 : auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit));
     if (sp > ktiles) sp = ktiles;
     if (sp > fit) sp = fit;
     if (sp < 1) sp = 1;
@@ -612,7 +633,8 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
     p.group_m = 8;
     p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
     p.conv = c.g;
-    hipError_t e = (c.g.Cin % 16 == 0 ? ki->launch_im2row : ki->launch_im2row_runs)(p, st);
+    p.vecA = aligned16(filter, c.N, 4) ? 1 : 0;
+    hipError_t e = conv_fused_launcher(ki, c, image_aligned)(p, st);
     if (e != hipSuccess) return (int)e;
     if (p.split > 1) {
         e = launch_reduce(MI_GEMM_F32, workspace, output, p.M, p.N, p.ldc, p.split, p.alpha_bits, p.beta_bits, p.use_beta, st);

@@ -18,6 +18,14 @@
 // rows of 147 floats) are staged without registers.  Edge tiles and a partial
 // last K step go through guarded loads and registers into the same layout.
 //
+// IM2ROW: the K-contiguous operand B is the im2row matrix of a channels-last image (paper Sec.
+// "Rectangular Matrices"), staged from the image in place.  Cin is a multiple of the K step, so a
+// step lies inside one filter tap and a tile row (an output pixel) is one 16-byte-aligned run of the
+// image.  Every lane always issues its transfer (the counting of outstanding transfers relies on
+// it): a lane whose tap falls outside the image reads the nearest pixel inside instead and, once
+// its transfer has landed, overwrites those 16 bytes of LDS with zeros before the barrier that
+// publishes the stage.
+//
 // With NSTAGE stages, NSTAGE-1 K steps are in flight while one is multiplied;
 // a short K loop (the im2row GEMMs with K of a few hundred) is fetched whole
 // before the first MFMA.
@@ -139,7 +147,27 @@ struct Dma32Micro {
     }
 };
 
-template <class T>
+// Position in K of an im2row K step: filter tap (r, s) and first channel c, advanced one step at a time.
+struct TapIter {
+    int r, s, c;
+    __device__ __forceinline__ void start(int k, const Im2row &g)
+    {
+        const int tap = k / g.Cin;
+        c = k - tap * g.Cin;
+        r = tap / g.kw;
+        s = tap - r * g.kw;
+    }
+    __device__ __forceinline__ void advance(int bk, const Im2row &g)
+    {
+        c += bk;
+        if (c == g.Cin) {
+            c = 0;
+            if (++s == g.kw) { s = 0; ++r; }
+        }
+    }
+};
+
+template <class T, bool IM2ROW = false>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params p)
 {
     typedef F32 DT;
@@ -174,9 +202,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
     const float *__restrict__ B = (const float *)p.B;
     // tile rows all inside the matrix, and a lane's 32-bit byte offset inside a block cannot overflow
     const bool in_a = (m0 + BM <= p.M) && (p.lda < (1 << 26));
-    const bool in_b = (n0 + BN <= p.N) && (p.ldb < (1 << 26));
+    const bool in_b = IM2ROW || ((n0 + BN <= p.N) && (p.ldb < (1 << 26)));   // IM2ROW: rows beyond N read row N-1, as zeros
     // rows are 16-byte aligned (a moved tile of A may start at any m)
-    const bool a16 = p.vecA != 0 && (m0 % 4 == 0), b16 = p.vecB != 0;
+    const bool a16 = p.vecA != 0 && (m0 % 4 == 0), b16 = IM2ROW || p.vecB != 0;
 
     // ---- staging.  A stage is cut into 1 KiB blocks, block `blk` of an operand belongs to wave
     // blk % NW.  16-byte path: one transfer per block.  4-byte path: four 256-byte transfers.
@@ -190,6 +218,58 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
     const uint32_t b_off16 = (uint32_t)(((int64_t)b_row_in * p.ldb + b_ch * 4) * 4);
     static_assert(T::B_R4 % T::B_RP256 == 0 && (NW * T::B_R4 / T::B_RP256) % T::B_CPR == 0,
                   "B swizzle must repeat every NW blocks");
+
+    // IM2ROW: the pixels this lane stages (one per transfer j): image row / column of the pixel's tap
+    // (0, 0), its image (b*H, so that an image row index is one addition), whether the row exists
+    constexpr int PJ = IM2ROW ? T::B_J : 1;
+    int pix_ih0[PJ], pix_iw0[PJ], pix_bh[PJ];
+    bool pix_ok[PJ];
+    if constexpr (IM2ROW) {
+        const int per_image = p.conv.Hout * p.conv.Wout;
+#pragma unroll
+        for (int j = 0; j < T::B_J; ++j) {
+            int n = n0 + (wave + NW * j) * T::B_R4 + b_row_in;
+            pix_ok[j] = n < p.N;
+            n = n < p.N ? n : p.N - 1;
+            const int b = n / per_image, rem = n - b * per_image;
+            const int oh = rem / p.conv.Wout, ow = rem - oh * p.conv.Wout;
+            pix_ih0[j] = oh * p.conv.stride_h - p.conv.pad_h;
+            pix_iw0[j] = ow * p.conv.stride_w - p.conv.pad_w;
+            pix_bh[j] = b * p.conv.H;
+        }
+    }
+    TapIter tap_stage, tap_fix;                                 // next step to stage / to publish
+    if constexpr (IM2ROW) {
+        tap_stage.start(kt_begin * BK, p.conv);
+        tap_fix = tap_stage;
+    }
+    // all B transfers of one K step: the lane's chunk of its pixel's tap, clamped into the image
+    auto stage_b_im2row = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < T::B_J; ++j) {
+            const int blk = wave + NW * j;
+            if (T::B_BLK % NW != 0 && blk >= T::B_BLK) break;
+            int ih = pix_ih0[j] + tap_stage.r, iw = pix_iw0[j] + tap_stage.s;
+            ih = ih < 0 ? 0 : (ih >= p.conv.H ? p.conv.H - 1 : ih);
+            iw = iw < 0 ? 0 : (iw >= p.conv.W ? p.conv.W - 1 : iw);
+            const uint32_t off = (uint32_t)((((int64_t)(pix_bh[j] + ih) * p.conv.W + iw) * p.conv.Cin + tap_stage.c + b_ch * 4) * 4);
+            lds_dma16(B, off, lds_base + buf * T::STAGE + T::A_BYTES + blk * 1024);
+        }
+        tap_stage.advance(BK, p.conv);
+    };
+    // after this wave's transfers of the step have landed: zeros where the tap is outside the image
+    auto fix_b_im2row = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < T::B_J; ++j) {
+            const int blk = wave + NW * j;
+            if (T::B_BLK % NW != 0 && blk >= T::B_BLK) break;
+            const bool inside = pix_ok[j] && (uint32_t)(pix_ih0[j] + tap_fix.r) < (uint32_t)p.conv.H &&
+                                (uint32_t)(pix_iw0[j] + tap_fix.s) < (uint32_t)p.conv.W;
+            if (!inside) *(v4i *)(smem + buf * T::STAGE + T::A_BYTES + blk * 1024 + lane * 16) = v4i{0, 0, 0, 0};
+        }
+        tap_fix.advance(BK, p.conv);
+        __builtin_amdgcn_s_waitcnt(0xc07f);                     // lgkmcnt(0): the zeros are in LDS before the barrier
+    };
 
     // number of transfer instructions this wave issues per fully direct stage (for the counter)
     int my_blocks = 0;
@@ -256,7 +336,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
     auto stage_tiles = [&](int kt, int buf) {
         const bool kfull = ((kt + 1) * BK <= p.K);
         stage_a(kt, buf, in_a && kfull);
-        stage_b(kt, buf, in_b && kfull);
+        if constexpr (IM2ROW) stage_b_im2row(buf);              // steps are staged in order
+        else stage_b(kt, buf, in_b && kfull);
     };
 
     const int frow = lane & 31, fgrp = lane >> 5;
@@ -330,6 +411,10 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
                     lds_dma4(ab + j * a_blk + a_q[q], (uint32_t)lane * 4, la + j * NW * 1024 + q * 256);
             }
         }
+        if constexpr (IM2ROW) {
+            stage_b_im2row(buf);
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < T::B_J; ++j) {
             if (T::B_BLK % NW != 0 && wave + NW * j >= T::B_BLK) break;
@@ -350,6 +435,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
             const int nxt = (buf + 1 == NS) ? 0 : buf + 1;
             steps_but_last(buf);
             wait_transfers_upto((NS - 2) * my_blocks);
+            if constexpr (IM2ROW) fix_b_im2row(nxt);
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             stage_direct(a16c, b16c, kt_begin + i + NS, buf);
@@ -369,6 +455,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
             const int staged = nkt < NS ? nkt : NS;
             wait_transfers_upto(staged <= nfast ? (staged - 1) * my_blocks : 0);
         }
+        if constexpr (IM2ROW) fix_b_im2row(0);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         load_frags(0, 0, fa[0], fb[0]);
@@ -387,6 +474,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma32(const Params
                 int last = i + NS - 1;
                 last = last < nkt - 1 ? last : nkt - 1;
                 wait_transfers_upto(last < nfast ? (last - (i + 1)) * my_blocks : 0);
+                if constexpr (IM2ROW) fix_b_im2row(nxt);
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
                 if (i + NS < nkt) stage_tiles(kt_begin + i + NS, buf);

@@ -115,9 +115,28 @@ static hipError_t launch_tile_dma32(const Params &p, hipStream_t stream)
 }
 
 template <class T>
+static hipError_t launch_tile_dma32_im2row(const Params &p, hipStream_t stream)
+{
+    static bool attr_done[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma32<T, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL((gemm_kernel_dma32<T, true>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+template <class T>
 static constexpr KernelInfo info_dma32(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, eff_pct, floor_ns, setup_ns, &solo_dma32<T>, T::MINB};
+    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, eff_pct, floor_ns, setup_ns,
+                      &solo_dma32<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 0, 0, &launch_tile_dma32_im2row<T>, nullptr};
 }
 
 template <class T>

@@ -66,6 +66,40 @@ def test_fused_path_on_every_register_direct_kernel():
             assert got == kid
 
 
+DMA_GEOMS = [
+    (2, 12, 10, 32, 70, 3, 3, 1, 1, 1, 1),     # padding on every side; 240 pixels and 70 channels: ragged tiles
+    (1, 20, 18, 64, 130, 5, 5, 2, 2, 2, 2),    # stride 2, two K steps per tap
+    (1, 9, 9, 32, 64, 1, 1, 1, 1, 0, 0),       # 1 x 1 filter
+    (3, 7, 5, 96, 40, 3, 2, 1, 2, 1, 0),       # fewer pixels (fewer than a 64-row tile in one case) than tile rows
+]
+
+
+def test_fused_path_on_the_direct_to_lds_kernels():
+    """Cin a multiple of 32: the direct-to-LDS fp32 kernels stage the image in place (taps outside the image
+    are read from the nearest pixel inside and zeroed in LDS)."""
+    kernels = [i for i in range(mg.gemm_kernel_count(mg.F32)) if "_dma" in mg.gemm_kernel_name(mg.F32, i)]
+    assert len(kernels) >= 3
+    for kid in kernels:
+        for i, geom in enumerate(DMA_GEOMS):
+            took, got, _ = run_conv(geom, 7800 + 10 * kid + i, 1.5, 0.5, path=1, kernel_id=kid, expect_path=1)
+            assert got == kid
+        _, _, sp = run_conv(DMA_GEOMS[1], 7900 + kid, 1.0, 0.0, path=1, kernel_id=kid, split=3, workspace="split", expect_path=1)
+        assert sp == 3
+    # an image that is only 4-byte aligned goes to the register-direct kernels
+    geom = DMA_GEOMS[0]
+    Hout, Wout, M, N, K = mg.conv2d_im2row_shape(*geom)
+    image, filt, _ = wl.conv_tensors_f32(7950, geom[0], geom[1], geom[2], geom[3], geom[4], geom[5], geom[6], Hout, Wout)
+    buf = torch.zeros(image.size + 8, device="cuda")
+    d_image = buf[1:1 + image.size]
+    d_image.copy_(torch.from_numpy(image.reshape(-1)))
+    d_out = torch.zeros(M * N, device="cuda")
+    mg.conv2d_im2row_f32(*geom, 1.0, d_image, torch.from_numpy(filt).cuda(), 0.0, d_out)
+    torch.cuda.synchronize()
+    assert mg.conv2d_im2row_last_path() == 1 and "_reg" in mg.gemm_kernel_name(mg.F32, mg.gemm_last_kernel_id())
+    ref = oracle.conv2d_nhwc_f32(image, filt, (geom[7], geom[8]), (geom[9], geom[10]))
+    assert oracle.normalised_error(d_out.cpu().numpy().reshape(M, N).astype(np.float64), ref.reshape(M, N), K, 1.0, 1.0) <= TOL
+
+
 def test_fused_path_with_k_split_and_without_workspace():
     for kid in _fused_kernels():
         _, _, sp = run_conv(GEOMS[3], 7200 + kid, 1.0, -0.5, path=1, kernel_id=kid, split=3, workspace="split", expect_path=1)
