@@ -144,7 +144,8 @@ const char *gemm_ex_status_string(int status);
  *       + beta * output[b][oh][ow][co]
  *   with zeros for image positions outside [0,H) x [0,W), no filter flip; beta == 0: output is not read.
  * When the image is smaller than 2 GiB (and, unless Cin is a multiple of 16, kh*kw*Cin < 2^22) the
- * GEMM kernels read the im2row matrix from the image in place (it is never formed).  Otherwise, or
+ * GEMM kernels read the im2row matrix from the image in place (it is never formed); with Cin a
+ * multiple of 32 and a 16-byte aligned image also the kernels that stage tiles in LDS do.  Otherwise, or
  * when the timing model expects it to be faster and the workspace has room, the matrix is written
  * into the workspace (M*K floats) and the GEMM runs on it.  conv2d_im2row_workspace_bytes gives a workspace
  * that suffices for either; a smaller one (or none) restricts the call to the in-place path and
