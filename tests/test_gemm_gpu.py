@@ -253,6 +253,28 @@ def test_every_im2row_table_shape_f32(layout):
         check_case("f32", layout, M, N, K, 1.0, 0.0, seed=4200 + idx)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_resnet50_table_shapes_in_16_and_8_bit(dtype):
+    """The 20 ResNet50 v1.5 GEMMs in the other data types, automatic selection (register-direct and
+    direct-to-LDS kernels of those types), alternating layouts."""
+    for idx, (M, N, K) in enumerate(wl.RESNET50_IM2ROW):
+        check_case(dtype, LAYOUTS[idx % 2], M, N, K, 1, 0, seed=4300 + idx)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_random_shapes_automatic_selection(dtype):
+    """Seeded random small problems with padded leading dimensions and operands off 16-byte alignment:
+    whatever the selector picks must agree with the oracle."""
+    rng = np.random.default_rng(4400)
+    for idx in range(24):
+        M, N = int(rng.integers(1, 400)), int(rng.integers(1, 400))
+        K = int(rng.integers(1, 700)) if idx % 3 else int(rng.integers(700, 5000))
+        pad = tuple(int(x) for x in rng.integers(0, 5, 3))
+        offsets = tuple(int(x) for x in rng.integers(0, 4, 3)) if idx % 2 else (0, 0, 0)
+        a, b = ((1, 0), (2, -1), (1, 1))[idx % 3]
+        check_case(dtype, LAYOUTS[idx % 2], M, N, K, a, b, seed=4400 + idx, pad=pad, offsets=offsets)
+
+
 def test_other_table_shapes_f32():
     """A few of the remaining rows of the two im2row tables (tiny K, skinny M, wide N)."""
     for idx, (M, N, K) in enumerate([wl.VGG16_IM2ROW[0], wl.RESNET50_IM2ROW[1], wl.RESNET50_IM2ROW[12],
