@@ -87,19 +87,27 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
     } else {
         const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
         const double wgs = tiles * split;
-        // workgroups are dealt to free slots as they come, so beyond one round the count is fractional
-        double rounds = wgs / ((double)NUM_CU * occ);
-        rounds = rounds <= 1.0 ? 1.0 : (double)ceil_div((int64_t)(rounds * 4.0), 1) / 4.0;
-        double resident = wgs / NUM_CU;                                  // workgroups sharing a CU, on average
-        if (resident < 1.0) resident = 1.0;
-        if (resident > occ) resident = occ;
         const double mfma_step = 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
-        double step = resident * mfma_step;
         double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
         if (M < ki->BM || N < ki->BN) floor_us *= kGuardedStepFactor;
-        if (step < floor_us) step = floor_us;
-        if (!aligned && ki->unaligned_pct > 0) step *= 100.0 / ki->unaligned_pct;
-        main_us = rounds * steps * step;
+        // time of one K step on a CU that runs `resident` workgroups side by side
+        auto step_us = [&](double resident) {
+            double step = resident * mfma_step;
+            if (step < floor_us) step = floor_us;
+            if (!aligned && ki->unaligned_pct > 0) step *= 100.0 / ki->unaligned_pct;
+            return step;
+        };
+        // whole rounds with every slot of every CU taken, then the rest: fewer workgroups per CU, each of
+        // which runs faster than in a full round (alone on its CU: as fast as its latency allows)
+        const double slots = (double)NUM_CU * occ;
+        const double full = (double)(int64_t)(wgs / slots);
+        const double rest = wgs - full * slots;
+        main_us = full * steps * step_us(occ);
+        if (rest > 0.0) {
+            double resident = (double)ceil_div((int64_t)rest, NUM_CU);
+            if (full == 0.0 && rest >= NUM_CU) resident = rest / NUM_CU;     // a single partial round: the average share
+            main_us += steps * step_us(resident);
+        }
         const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
         if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
     }
