@@ -36,10 +36,11 @@ struct Choice { int id; int split; int ktiles_per_split; };
 // predicted time is
 //     launch + fixed cost + main + reduce(split)
 // Kernels that stage tiles in LDS:
-//     main    = max(rounds * steps * step_time, staged_bytes / staging_bandwidth)
-//     rounds  = tiles*split / (CUs * workgroups per CU), at least 1
+//     main    = max(sum over rounds of steps * step_time(r), staged_bytes / staging_bandwidth)
+//     rounds  = whole rounds that fill every slot (CUs * workgroups per CU), then one partial round with
+//               r = fewer workgroups per CU, which run faster
 //     steps   = ceil(K steps / split)
-//     step_time = max(co-resident workgroups * MFMA time of one K step, latency of a step);
+//     step_time(r) = max(r co-resident workgroups * MFMA time of one K step, latency of a step);
 //                 the latency is 2.2 times longer when a dimension is smaller than the tile, because
 //                 such a tile cannot be moved inside the matrix and is staged through registers
 // Register-direct kernels (every wave streams its own operands):
