@@ -138,15 +138,20 @@ bool can_address(const KernelInfo *ki, int64_t lda, int64_t ldb)
 
 // Best (configuration, split) over the configurations open to automatic selection (prio > 0).
 int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t max_split_bytes_per_mn,
-                bool aligned, bool transposed)
+                bool aligned, bool a_kc, bool b_nc)
 {
     const int n = kernel_count(dtype);
     int best = -1;
     double best_us = 0.0;
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        // transposed operands: every configuration that takes them; otherwise those open to selection
-        if (transposed ? !ki->transposed_ok : ki->prio <= 0) continue;
+        // transposed operands: every configuration that takes them (a K-contiguous A with the canonical B
+        // also the direct kernels built for it); otherwise those open to selection
+        // (for that case the staged configurations that are closed to selection stay out: their constants
+        // are not calibrated against the direct kernels)
+        const bool takes = (a_kc && !b_nc) ? (ki->prio > 0 && (ki->a_kc_ok || ki->transposed_ok))
+                                           : (a_kc || b_nc) ? ki->transposed_ok != 0 : ki->prio > 0;
+        if (!takes) continue;
         if (!can_address(ki, lda, ldb)) continue;
         const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned);
         const double t = predict_us(dtype, ki, M, N, K, s, aligned);
@@ -156,7 +161,7 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
 }
 
 Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws,
-              bool aligned, bool transposed = false)
+              bool aligned, bool a_kc = false, bool b_nc = false)
 {
     Choice c;
     const Forced f = g_forced[dtype];
@@ -166,8 +171,9 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     if (fit > MAX_SPLIT) fit = MAX_SPLIT;
     if (fit < 1) fit = 1;
     const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb) &&
-                        (!transposed || kernel_info(dtype, f.id)->transposed_ok);
-    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, transposed);
+                        (!(a_kc || b_nc) || kernel_info(dtype, f.id)->transposed_ok ||
+                         (a_kc && !b_nc && kernel_info(dtype, f.id)->a_kc_ok));
+    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
     int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned);
@@ -236,7 +242,7 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     }
 
     const bool vec_a = aligned16(Ac, ldac, es), vec_b = aligned16(Bc, ldbc, es);
-    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr, vec_a && vec_b, a_kc || b_nc);
+    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr, vec_a && vec_b, a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, ch.id);
 
     Params p;
@@ -601,7 +607,7 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
         if (!explicit_fits) return -18;
         fused = false;
     } else if (g_conv_forced_path == 0 && explicit_fits && g_forced[MI_GEMM_F32].id < 0) {
-        const int gid = auto_kernel(MI_GEMM_F32, c.N, c.M, c.K, c.N, c.K, 1, true, false);
+        const int gid = auto_kernel(MI_GEMM_F32, c.N, c.M, c.K, c.N, c.K, 1, true, false, false);
         const double explicit_us = predict_us(MI_GEMM_F32, kernel_info(MI_GEMM_F32, gid), c.N, c.M, c.K, 1) + kIm2rowFixedUs +
                                    (double)matrix_bytes / kIm2rowBytesPerUs;
         if (explicit_us < fused_us) fused = false;

@@ -232,7 +232,10 @@ template <> struct Mma16<I8> {
     }
 };
 
-template <class T>
+// A_KC: the operand A has K contiguous as well (a transposed A: op(A) = A^T of a column-major problem,
+// or the weight matrix of x W^T in row-major terms).  Its tile is then staged exactly like B's (tile
+// rows of K, chunks swizzled by row) and its fragments are plain 16-byte reads; no transposing reads.
+template <class T, bool A_KC = false>
 struct DmaMicro16 {
     typedef typename T::DT DT;
     typedef typename Mma16<DT>::accv accv;
@@ -242,7 +245,7 @@ struct DmaMicro16 {
     static constexpr int ACC = 4;
     static_assert(T::KSTEPS % 2 == 0 && TM % 2 == 0, "k steps of 4 chunks, two row halves");
     v4i fa[2][HM], fb[2][TN];
-    uint32_t aoff[TM], boff[T::KSTEPS / 2];
+    uint32_t aoff[A_KC ? T::KSTEPS / 2 : TM], boff[T::KSTEPS / 2];
 
     __device__ __forceinline__ void init(int lane, int wm0, int wn0)
     {
@@ -252,6 +255,13 @@ struct DmaMicro16 {
 #pragma unroll
         for (int ks = 0; ks < T::KSTEPS / 2; ++ks)
             boff[ks] = T::A_BYTES + (wn0 + r) * T::B_ROWB + (((4 * ks + g) ^ x) << 4);
+        if constexpr (A_KC) {
+            // A staged like B: row wm0 + 16*i + r of the A region, same chunk and swizzle
+#pragma unroll
+            for (int ks = 0; ks < T::KSTEPS / 2; ++ks)
+                aoff[ks] = (wm0 + r) * T::B_ROWB + (((4 * ks + g) ^ x) << 4);
+            return;
+        }
         // A: the 16-lane group g reads k group g of the 16 rows of a block; inside it, lane r
         // addresses k-row r/LPR and the (r%LPR)-th 8-byte piece of the 16 m
         const int kr = r / T::LPR, ml = r % T::LPR;
@@ -267,8 +277,10 @@ struct DmaMicro16 {
     {
         const int ks = s >> 1, mh = s & 1;
 #pragma unroll
-        for (int i = 0; i < HM; ++i)
-            fa[s & 1][i] = DmaMicro<T>::read_a(stage + aoff[mh * HM + i] + (4 * KCH * ks) * A_ROWB);
+        for (int i = 0; i < HM; ++i) {
+            if constexpr (A_KC) fa[s & 1][i] = *(const v4i *)(stage + aoff[ks] + (mh * HM + i) * 16 * T::B_ROWB);
+            else fa[s & 1][i] = DmaMicro<T>::read_a(stage + aoff[mh * HM + i] + (4 * KCH * ks) * A_ROWB);
+        }
         if (mh == 0) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) fb[ks & 1][j] = *(const v4i *)(stage + boff[ks] + j * 16 * T::B_ROWB);
@@ -323,7 +335,7 @@ struct DmaMicro16 {
     }
 };
 
-template <class T, class Micro = DmaMicro<T>>
+template <class T, class Micro = DmaMicro<T>, bool A_KC = false>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p)
 {
     typedef typename T::DT DT;
@@ -347,7 +359,8 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     // least one tile wide and the moved tile keeps the 16-byte alignment of its rows: it then takes
     // the direct transfers of an interior tile and stores only the part no other tile owns.
     const int m_own = tm * BM, n_own = tn * BN;
-    const int m0 = (m_own + BM > p.M && p.M >= BM && (p.M * ES) % 16 == 0) ? p.M - BM : m_own;
+    // (A_KC: rows of A are lda apart, so a moved tile is as aligned as any other)
+    const int m0 = (m_own + BM > p.M && p.M >= BM && (A_KC || (p.M * ES) % 16 == 0)) ? p.M - BM : m_own;
     const int n0 = (n_own + BN > p.N && p.N >= BN) ? p.N - BN : n_own;
 
     const int z = blockIdx.y;
@@ -363,25 +376,30 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
 
     // ---- staging: which chunk of the A and B tiles this lane moves in transfer j
     // A: transfer block b = wave + NW*j covers k-rows b*A_ROWS_PER_INST ...; lane -> (row, physical chunk)
-    const int a_row_in = lane / A_CPR, a_pch = lane % A_CPR;
+    // (A_KC: like B, transfer block b covers B_ROWS_PER_INST tile rows m)
+    const int a_row_in = A_KC ? lane / T::B_CPR : lane / A_CPR, a_pch = A_KC ? lane % T::B_CPR : lane % A_CPR;
     // B: transfer block b covers B_ROWS_PER_INST tile rows; lane -> (row, physical chunk)
     const int b_row_in = lane / T::B_CPR, b_pch = lane % T::B_CPR;
     // The swizzle term of a lane's row does not depend on j (NW transfers apart the row pattern
     // repeats), so a lane's byte offset from the block's first element is the same in every transfer.
     static_assert((NW * T::A_ROWS_PER_INST) % T::SWZ_PERIOD == 0, "A swizzle must repeat every NW blocks");
     static_assert((NW * T::B_ROWS_PER_INST) % (T::B_RP256 * T::B_CPR) == 0, "B swizzle must repeat every NW blocks");
-    const int a_ch = a_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + a_row_in);
+    const int a_ch = A_KC ? a_pch ^ (((wave * T::B_ROWS_PER_INST + a_row_in) / T::B_RP256) % T::B_CPR)
+                          : a_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + a_row_in);
     const int b_ch = b_pch ^ (((wave * T::B_ROWS_PER_INST + b_row_in) / T::B_RP256) % T::B_CPR);
-    const uint32_t a_lane_off = (uint32_t)(((int64_t)a_row_in * p.lda + a_ch * (16 / ES)) * ES);
+    const uint32_t a_lane_off = (uint32_t)(((int64_t)a_row_in * p.lda + a_ch * (16 / ES)) * ES);   // 16/ES == KCH
     const uint32_t b_lane_off = (uint32_t)(((int64_t)b_row_in * p.ldb + b_ch * KCH) * ES);
-    const int64_t a_blk_stride = (int64_t)NW * T::A_ROWS_PER_INST * p.lda * ES;   // bytes between transfers j, j+1
+    constexpr int A_RPI = A_KC ? T::B_ROWS_PER_INST : T::A_ROWS_PER_INST;          // tile rows (m or k) per transfer
+    const int64_t a_blk_stride = (int64_t)NW * A_RPI * p.lda * ES;                 // bytes between transfers j, j+1
     const int64_t b_blk_stride = (int64_t)NW * T::B_ROWS_PER_INST * p.ldb * ES;
-    const unsigned char *a_wave = (const unsigned char *)A + ((int64_t)wave * T::A_ROWS_PER_INST * p.lda + m0) * ES;
+    const int64_t a_step = A_KC ? (int64_t)BK * ES : (int64_t)BK * p.lda * ES;      // bytes from one K step to the next
+    const unsigned char *a_wave = A_KC ? (const unsigned char *)A + ((int64_t)(m0 + wave * A_RPI) * p.lda) * ES
+                                       : (const unsigned char *)A + ((int64_t)wave * A_RPI * p.lda + m0) * ES;
     const unsigned char *b_wave = (const unsigned char *)B + ((int64_t)(n0 + wave * T::B_ROWS_PER_INST) * p.ldb) * ES;
 
     // all transfers of one K step, operands fully inside the matrices and 16-byte aligned
     auto stage_dma = [&](int kt, int buf) {
-        const unsigned char *ab = a_wave + (int64_t)kt * BK * p.lda * ES;
+        const unsigned char *ab = a_wave + (int64_t)kt * a_step;
         const unsigned char *bb = b_wave + (int64_t)kt * BK * ES;
         const uint32_t la = lds_base + buf * T::STAGE + wave * 1024;
 #pragma unroll
@@ -396,7 +414,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
         const int k0 = kt * BK;
         const uint32_t sbase = buf * T::STAGE;
         if (dma_a) {
-            const unsigned char *ab = a_wave + (int64_t)kt * BK * p.lda * ES;
+            const unsigned char *ab = a_wave + (int64_t)kt * a_step;
 #pragma unroll
             for (int j = 0; j < T::A_INST; ++j)
                 lds_dma16(ab + j * a_blk_stride, a_lane_off, lds_base + sbase + (wave + NW * j) * 1024);
@@ -404,6 +422,15 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
 #pragma unroll
             for (int j = 0; j < T::A_INST; ++j) {
                 const int blk = wave + NW * j;
+                if constexpr (A_KC) {
+                    const int r = blk * A_RPI + a_row_in;                      // tile row m
+                    const int k = k0 + a_ch * KCH;
+                    const elt *src = A + (int64_t)(m0 + r) * p.lda + k;
+                    int valid = (m0 + r < p.M) ? (p.K - k) : 0;
+                    valid = valid > KCH ? KCH : valid;
+                    *(v4i *)(smem + sbase + blk * 1024 + lane * 16) = guarded_chunk<DT>(src, valid);
+                    continue;
+                }
                 const int k = blk * T::A_ROWS_PER_INST + a_row_in;             // tile-local k-row
                 const int m = m0 + a_ch * (16 / ES);
                 const elt *src = A + (int64_t)(k0 + k) * p.lda + m;

@@ -108,3 +108,25 @@ def test_gemm_ex_untransposed_is_the_plain_entry_point():
     assert mg.gemm_last_kernel_id() == k1
     torch.cuda.synchronize()
     assert torch.equal(c1, c2)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_k_contiguous_a_on_the_direct_kernels(dtype):
+    """op(A) = A^T in column-major terms, or x W^T in row-major terms (both operands with K contiguous): the
+    direct-to-LDS kernels stage A like B.  Aligned multi-tile shapes (transfers only), shapes whose last tile
+    is moved back, odd leading dimensions (guarded staging) and a K split, on every such kernel; and the
+    automatic choice must be one of them for a large problem."""
+    direct = [i for i in range(mg.gemm_kernel_count(DT[dtype])) if mg.gemm_kernel_name(DT[dtype], i).endswith("_dma16")]
+    assert len(direct) >= 3
+    a, b = (3, -2) if dtype == "i8" else (1.5, 0.5)
+    for kid in direct:
+        k, _ = _case(dtype, "col", 1, 0, 512, 384, 256, a, b, seed=7600 + kid, kernel_id=kid)
+        assert k == kid
+        k, _ = _case(dtype, "row", 0, 1, 640, 512, 320, a, b, seed=7610 + kid, kernel_id=kid)
+        assert k == kid
+        _case(dtype, "col", 1, 0, 400, 336, 448, a, b, seed=7620 + kid, kernel_id=kid)            # edge tiles moved back
+        _case(dtype, "col", 1, 0, 300, 270, 200, a, b, seed=7630 + kid, kernel_id=kid, pad=(3, 5, 1))
+        k, s = _case(dtype, "row", 0, 1, 256, 256, 2048, a, b, seed=7640 + kid, kernel_id=kid, split=4)
+        assert (k, s) == (kid, 4)
+    k, _ = _case(dtype, "row", 0, 1, 2048, 2048, 1024, 1, 0, seed=7650)
+    assert mg.gemm_kernel_name(DT[dtype], k).endswith("_dma16")
