@@ -278,6 +278,8 @@ def main():
                     Case("f32", "col", 4096, 4096, 4096, 1.0, 0.0, 3600, trans=trans))
         measure("transposed operands (beyond the configurations)",
                 Case("f16", "col", 4096, 4096, 4096, 1.0, 0.0, 3601, trans=(1, 0)))
+        measure("transposed operands (beyond the configurations)",
+                Case("i8", "col", 4096, 4096, 4096, 1, 0, 3602, trans=(1, 0)))
         torch.cuda.empty_cache()
         for i, (M, N, K) in enumerate(wl.IM2ROW_HEADLINE):
             for layout in ("col", "row"):
