@@ -143,14 +143,18 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
     const int n = kernel_count(dtype);
     int best = -1;
     double best_us = 0.0;
+    // does a configuration open to selection take these operand orientations at its normal speed?
+    auto direct = [&](const KernelInfo *ki) { return (!a_kc || ki->a_kc_ok) && (!b_nc || ki->b_nc_ok); };
+    bool any_direct = false;
+    for (int id = 0; id < n; ++id) any_direct = any_direct || (kernel_info(dtype, id)->prio > 0 && direct(kernel_info(dtype, id)));
     for (int id = 0; id < n; ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        // transposed operands: every configuration that takes them (a K-contiguous A with the canonical B
-        // also the direct kernels built for it); otherwise those open to selection
-        // (for that case the staged configurations that are closed to selection stay out: their constants
-        // are not calibrated against the direct kernels)
-        const bool takes = (a_kc && !b_nc) ? (ki->prio > 0 && (ki->a_kc_ok || ki->transposed_ok))
-                                           : (a_kc || b_nc) ? ki->transposed_ok != 0 : ki->prio > 0;
+        // canonical operands: the configurations open to selection.  Transposed operands: where the data type
+        // has direct kernels for that orientation, those and the staged ones open to selection (the constants
+        // of the others are not calibrated against the direct kernels); else every staged configuration
+        const bool takes = !(a_kc || b_nc) ? ki->prio > 0
+                           : any_direct    ? ki->prio > 0 && (direct(ki) || ki->transposed_ok)
+                                           : ki->transposed_ok != 0;
         if (!takes) continue;
         if (!can_address(ki, lda, ldb)) continue;
         const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned);
@@ -172,7 +176,7 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     if (fit < 1) fit = 1;
     const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb) &&
                         (!(a_kc || b_nc) || kernel_info(dtype, f.id)->transposed_ok ||
-                         (a_kc && !b_nc && kernel_info(dtype, f.id)->a_kc_ok));
+                         ((!a_kc || kernel_info(dtype, f.id)->a_kc_ok) && (!b_nc || kernel_info(dtype, f.id)->b_nc_ok)));
     c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);

@@ -235,7 +235,10 @@ template <> struct Mma16<I8> {
 // A_KC: the operand A has K contiguous as well (a transposed A: op(A) = A^T of a column-major problem,
 // or the weight matrix of x W^T in row-major terms).  Its tile is then staged exactly like B's (tile
 // rows of K, chunks swizzled by row) and its fragments are plain 16-byte reads; no transposing reads.
-template <class T, bool A_KC = false>
+// B_NC: the operand B has N contiguous (a transposed B); its tile is then staged exactly like the
+// canonical A's (k-rows of BN elements, the same swizzle) and read with the transposing reads.
+// Square tiles only, so that both operands share the constants of that layout.
+template <class T, bool A_KC = false, bool B_NC = false>
 struct DmaMicro16 {
     typedef typename T::DT DT;
     typedef typename Mma16<DT>::accv accv;
@@ -245,16 +248,28 @@ struct DmaMicro16 {
     static constexpr int ACC = 4;
     static_assert(T::KSTEPS % 2 == 0 && TM % 2 == 0, "k steps of 4 chunks, two row halves");
     v4i fa[2][HM], fb[2][TN];
-    uint32_t aoff[A_KC ? T::KSTEPS / 2 : TM], boff[T::KSTEPS / 2];
+    uint32_t aoff[A_KC ? T::KSTEPS / 2 : TM], boff[B_NC ? TN : T::KSTEPS / 2];
+    static_assert(!B_NC || T::BM == T::BN, "a transposed B needs a square tile");
 
     __device__ __forceinline__ void init(int lane, int wm0, int wn0)
     {
         const int r = lane & 15, g = lane >> 4;
         // B: row wn0 + 16*j + r, logical chunk 4*ks + g; the swizzle of the row depends on r only
         const int x = (r / T::B_RP256) % T::B_CPR;
+        if constexpr (B_NC) {
+            // B staged like the canonical A: k group g of the 16 columns n of a block
+            const int kr = r / T::LPR, ml = r % T::LPR;
 #pragma unroll
-        for (int ks = 0; ks < T::KSTEPS / 2; ++ks)
-            boff[ks] = T::A_BYTES + (wn0 + r) * T::B_ROWB + (((4 * ks + g) ^ x) << 4);
+            for (int j = 0; j < TN; ++j) {
+                const int nbyte = (wn0 + 16 * j) * ES + 8 * ml;
+                const int ch = (nbyte >> 4) ^ T::a_swz(KCH * g + kr);
+                boff[j] = T::A_BYTES + (KCH * g + kr) * A_ROWB + (ch << 4) + (nbyte & 15);
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < T::KSTEPS / 2; ++ks)
+                boff[ks] = T::A_BYTES + (wn0 + r) * T::B_ROWB + (((4 * ks + g) ^ x) << 4);
+        }
         if constexpr (A_KC) {
             // A staged like B: row wm0 + 16*i + r of the A region, same chunk and swizzle
 #pragma unroll
@@ -283,7 +298,10 @@ struct DmaMicro16 {
         }
         if (mh == 0) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[ks & 1][j] = *(const v4i *)(stage + boff[ks] + j * 16 * T::B_ROWB);
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (B_NC) fb[ks & 1][j] = DmaMicro<T>::read_a(stage + boff[j] + (4 * KCH * ks) * A_ROWB);
+                else fb[ks & 1][j] = *(const v4i *)(stage + boff[ks] + j * 16 * T::B_ROWB);
+            }
         }
     }
 
@@ -335,9 +353,10 @@ struct DmaMicro16 {
     }
 };
 
-template <class T, class Micro = DmaMicro<T>, bool A_KC = false>
+template <class T, class Micro = DmaMicro<T>, bool A_KC = false, bool B_NC = false>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p)
 {
+    static_assert(!B_NC || T::BM == T::BN, "a transposed B needs a square tile");
     typedef typename T::DT DT;
     typedef typename DT::elt elt;
     typedef typename Micro::accv accv;
@@ -361,7 +380,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     const int m_own = tm * BM, n_own = tn * BN;
     // (A_KC: rows of A are lda apart, so a moved tile is as aligned as any other)
     const int m0 = (m_own + BM > p.M && p.M >= BM && (A_KC || (p.M * ES) % 16 == 0)) ? p.M - BM : m_own;
-    const int n0 = (n_own + BN > p.N && p.N >= BN) ? p.N - BN : n_own;
+    const int n0 = (n_own + BN > p.N && p.N >= BN && (!B_NC || (p.N * ES) % 16 == 0)) ? p.N - BN : n_own;
 
     const int z = blockIdx.y;
     const int kt_begin = z * p.ktiles_per_split;
@@ -379,28 +398,33 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
     // (A_KC: like B, transfer block b covers B_ROWS_PER_INST tile rows m)
     const int a_row_in = A_KC ? lane / T::B_CPR : lane / A_CPR, a_pch = A_KC ? lane % T::B_CPR : lane % A_CPR;
     // B: transfer block b covers B_ROWS_PER_INST tile rows; lane -> (row, physical chunk)
-    const int b_row_in = lane / T::B_CPR, b_pch = lane % T::B_CPR;
+    // (B_NC: like the canonical A, transfer block b covers A_ROWS_PER_INST k-rows)
+    const int b_row_in = B_NC ? lane / A_CPR : lane / T::B_CPR, b_pch = B_NC ? lane % A_CPR : lane % T::B_CPR;
     // The swizzle term of a lane's row does not depend on j (NW transfers apart the row pattern
     // repeats), so a lane's byte offset from the block's first element is the same in every transfer.
     static_assert((NW * T::A_ROWS_PER_INST) % T::SWZ_PERIOD == 0, "A swizzle must repeat every NW blocks");
     static_assert((NW * T::B_ROWS_PER_INST) % (T::B_RP256 * T::B_CPR) == 0, "B swizzle must repeat every NW blocks");
     const int a_ch = A_KC ? a_pch ^ (((wave * T::B_ROWS_PER_INST + a_row_in) / T::B_RP256) % T::B_CPR)
                           : a_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + a_row_in);
-    const int b_ch = b_pch ^ (((wave * T::B_ROWS_PER_INST + b_row_in) / T::B_RP256) % T::B_CPR);
+    const int b_ch = B_NC ? b_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + b_row_in)
+                          : b_pch ^ (((wave * T::B_ROWS_PER_INST + b_row_in) / T::B_RP256) % T::B_CPR);
     const uint32_t a_lane_off = (uint32_t)(((int64_t)a_row_in * p.lda + a_ch * (16 / ES)) * ES);   // 16/ES == KCH
     const uint32_t b_lane_off = (uint32_t)(((int64_t)b_row_in * p.ldb + b_ch * KCH) * ES);
     constexpr int A_RPI = A_KC ? T::B_ROWS_PER_INST : T::A_ROWS_PER_INST;          // tile rows (m or k) per transfer
     const int64_t a_blk_stride = (int64_t)NW * A_RPI * p.lda * ES;                 // bytes between transfers j, j+1
-    const int64_t b_blk_stride = (int64_t)NW * T::B_ROWS_PER_INST * p.ldb * ES;
+    constexpr int B_RPI = B_NC ? T::A_ROWS_PER_INST : T::B_ROWS_PER_INST;         // tile rows (k or n) per transfer
+    const int64_t b_blk_stride = (int64_t)NW * B_RPI * p.ldb * ES;
+    const int64_t b_step = B_NC ? (int64_t)BK * p.ldb * ES : (int64_t)BK * ES;
     const int64_t a_step = A_KC ? (int64_t)BK * ES : (int64_t)BK * p.lda * ES;      // bytes from one K step to the next
     const unsigned char *a_wave = A_KC ? (const unsigned char *)A + ((int64_t)(m0 + wave * A_RPI) * p.lda) * ES
                                        : (const unsigned char *)A + ((int64_t)wave * A_RPI * p.lda + m0) * ES;
-    const unsigned char *b_wave = (const unsigned char *)B + ((int64_t)(n0 + wave * T::B_ROWS_PER_INST) * p.ldb) * ES;
+    const unsigned char *b_wave = B_NC ? (const unsigned char *)B + ((int64_t)wave * B_RPI * p.ldb + n0) * ES
+                                       : (const unsigned char *)B + ((int64_t)(n0 + wave * B_RPI) * p.ldb) * ES;
 
     // all transfers of one K step, operands fully inside the matrices and 16-byte aligned
     auto stage_dma = [&](int kt, int buf) {
         const unsigned char *ab = a_wave + (int64_t)kt * a_step;
-        const unsigned char *bb = b_wave + (int64_t)kt * BK * ES;
+        const unsigned char *bb = b_wave + (int64_t)kt * b_step;
         const uint32_t la = lds_base + buf * T::STAGE + wave * 1024;
 #pragma unroll
         for (int j = 0; j < T::A_INST; ++j) lds_dma16(ab + j * a_blk_stride, a_lane_off, la + j * NW * 1024);
@@ -440,7 +464,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
             }
         }
         if (dma_b) {
-            const unsigned char *bb = b_wave + (int64_t)kt * BK * ES;
+            const unsigned char *bb = b_wave + (int64_t)kt * b_step;
 #pragma unroll
             for (int j = 0; j < T::B_INST; ++j)
                 lds_dma16(bb + j * b_blk_stride, b_lane_off, lds_base + sbase + T::A_BYTES + (wave + NW * j) * 1024);
@@ -448,6 +472,15 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_dma(const Params p
 #pragma unroll
             for (int j = 0; j < T::B_INST; ++j) {
                 const int blk = wave + NW * j;
+                if constexpr (B_NC) {
+                    const int k = blk * B_RPI + b_row_in;                      // tile-local k-row
+                    const int n = n0 + b_ch * (16 / ES);
+                    const elt *src = B + (int64_t)(k0 + k) * p.ldb + n;
+                    int valid = (k0 + k < p.K) ? (p.N - n) : 0;
+                    valid = valid > 16 / ES ? 16 / ES : valid;
+                    *(v4i *)(smem + sbase + T::A_BYTES + blk * 1024 + lane * 16) = guarded_chunk<DT>(src, valid);
+                    continue;
+                }
                 const int r = blk * T::B_ROWS_PER_INST + b_row_in;              // tile row n
                 const int k = k0 + b_ch * KCH;
                 const elt *src = B + (int64_t)(n0 + r) * p.ldb + k;

@@ -71,7 +71,8 @@ struct KernelInfo {
     // for Cin a multiple of the K step (a step lies in one filter tap), and for any Cin (element by element)
     hipError_t (*launch_im2row)(const Params &, hipStream_t);
     hipError_t (*launch_im2row_runs)(const Params &, hipStream_t);
-    int a_kc_ok;             // takes A with K contiguous and the canonical B (Params::a_kc), at its normal speed
+    int a_kc_ok;             // takes A with K contiguous (Params::a_kc) at its normal speed
+    int b_nc_ok;             // takes B with N contiguous (Params::b_nc) at its normal speed
 };
 
 int kernel_count(int dtype);                       // dtype: 0 fp32, 1 fp16, 2 int8, 3 bf16

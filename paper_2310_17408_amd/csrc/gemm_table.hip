@@ -90,27 +90,34 @@ static constexpr KernelInfo info_dma(const char *name, int prio, int eff_pct, in
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma<T, Micro>, prio, eff_pct, floor_ns,
                       setup_ns, &solo_dma<T, Micro>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 30};
 }
-// the 16x16-block micro-kernel: canonical A, or A with K contiguous (Params::a_kc)
-template <class T>
-static hipError_t launch_tile_dma16(const Params &p, hipStream_t stream)
+// the 16x16-block micro-kernel in one operand orientation: A canonical or with K contiguous
+// (Params::a_kc), B canonical or, on square tiles, with N contiguous (Params::b_nc)
+template <class T, bool A_KC, bool B_NC>
+static hipError_t launch_dma16_variant(const Params &p, hipStream_t stream)
 {
     static bool attr_done[64] = {false};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !attr_done[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma<T, DmaMicro16<T, false>, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma<T, DmaMicro16<T, true>, true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma<T, DmaMicro16<T, A_KC, B_NC>, A_KC, B_NC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done[dev] = true;
     }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
-    if (p.a_kc) hipLaunchKernelGGL((gemm_kernel_dma<T, DmaMicro16<T, true>, true>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
-    else hipLaunchKernelGGL((gemm_kernel_dma<T, DmaMicro16<T, false>, false>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((gemm_kernel_dma<T, DmaMicro16<T, A_KC, B_NC>, A_KC, B_NC>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
     return hipGetLastError();
+}
+template <class T>
+static hipError_t launch_tile_dma16(const Params &p, hipStream_t stream)
+{
+    if constexpr (T::BM == T::BN) {
+        if (p.b_nc) return p.a_kc ? launch_dma16_variant<T, true, true>(p, stream) : launch_dma16_variant<T, false, true>(p, stream);
+    } else {
+        if (p.b_nc) return hipErrorInvalidValue;        // the selector never asks for it (b_nc_ok == 0)
+    }
+    return p.a_kc ? launch_dma16_variant<T, true, false>(p, stream) : launch_dma16_variant<T, false, false>(p, stream);
 }
 template <class T>
 static constexpr KernelInfo info_dma16(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
@@ -118,6 +125,7 @@ static constexpr KernelInfo info_dma16(const char *name, int prio, int eff_pct, 
     KernelInfo k = info_dma<T, DmaMicro16<T>>(name, prio, eff_pct, floor_ns, setup_ns);
     k.launch = &launch_tile_dma16<T>;
     k.a_kc_ok = 1;
+    k.b_nc_ok = (T::BM == T::BN) ? 1 : 0;
     return k;
 }
 

@@ -130,3 +130,30 @@ def test_k_contiguous_a_on_the_direct_kernels(dtype):
         assert (k, s) == (kid, 4)
     k, _ = _case(dtype, "row", 0, 1, 2048, 2048, 1024, 1, 0, seed=7650)
     assert mg.gemm_kernel_name(DT[dtype], k).endswith("_dma16")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_n_contiguous_b_on_the_square_direct_kernels(dtype):
+    """op(B) = B^T in column-major terms (B with N contiguous), alone and together with a K-contiguous A: the
+    direct kernels with square tiles stage B like the canonical A (transposing LDS reads)."""
+    square = [i for i in range(mg.gemm_kernel_count(DT[dtype]))
+              if mg.gemm_kernel_name(DT[dtype], i).endswith("_dma16") and mg.gemm_kernel_tile(DT[dtype], i)[0] == mg.gemm_kernel_tile(DT[dtype], i)[1]]
+    assert len(square) >= 2
+    a, b = (3, -2) if dtype == "i8" else (1.5, 0.5)
+    for kid in square:
+        for ta in (0, 1):
+            k, _ = _case(dtype, "col", ta, 1, 512, 768, 256, a, b, seed=7700 + 2 * kid + ta, kernel_id=kid)
+            assert k == kid
+            _case(dtype, "col", ta, 1, 400, 336, 448, a, b, seed=7720 + 2 * kid + ta, kernel_id=kid)         # edge tiles moved back
+            _case(dtype, "col", ta, 1, 300, 270, 200, a, b, seed=7740 + 2 * kid + ta, kernel_id=kid, pad=(3, 5, 1))
+        k, _ = _case(dtype, "row", 1, 0, 640, 512, 320, a, b, seed=7760 + kid, kernel_id=kid)               # row-major: transa is the N-contiguous B
+        assert k == kid
+        k, s = _case(dtype, "col", 1, 1, 256, 256, 2048, a, b, seed=7770 + kid, kernel_id=kid, split=4)
+        assert (k, s) == (kid, 4)
+    # a tile that is not square cannot take it: the selector must replace it
+    odd = [i for i in range(mg.gemm_kernel_count(DT[dtype])) if mg.gemm_kernel_name(DT[dtype], i).endswith("128x64_w64x32_dma16")]
+    k, _ = _case(dtype, "col", 0, 1, 300, 270, 200, a, b, seed=7780, kernel_id=odd[0])
+    assert k != odd[0]
+    for ta in (0, 1):
+        k, _ = _case(dtype, "col", ta, 1, 2048, 2048, 1024, 1, 0, seed=7790 + ta)
+        assert mg.gemm_kernel_name(DT[dtype], k).endswith("_dma16")
