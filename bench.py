@@ -276,8 +276,9 @@ def main():
         for trans in ((1, 0), (0, 1), (1, 1)):
             measure("transposed operands (beyond the configurations)",
                     Case("f32", "col", 4096, 4096, 4096, 1.0, 0.0, 3600, trans=trans))
-        measure("transposed operands (beyond the configurations)",
-                Case("f16", "col", 4096, 4096, 4096, 1.0, 0.0, 3601, trans=(1, 0)))
+        for trans in ((1, 0), (0, 1), (1, 1)):
+            measure("transposed operands (beyond the configurations)",
+                    Case("f16", "col", 4096, 4096, 4096, 1.0, 0.0, 3601, trans=trans))
         measure("transposed operands (beyond the configurations)",
                 Case("i8", "col", 4096, 4096, 4096, 1, 0, 3602, trans=(1, 0)))
         torch.cuda.empty_cache()
