@@ -105,9 +105,8 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
         const double rest = wgs - full * slots;
         main_us = full * steps * step_us(occ);
         if (rest > 0.0) {
-            double resident = (double)ceil_div((int64_t)rest, NUM_CU);
-            if (full == 0.0 && rest >= NUM_CU) resident = rest / NUM_CU;     // a single partial round: the average share
-            main_us += steps * step_us(resident);
+            // the CUs that got the most workgroups finish last
+            main_us += steps * step_us((double)ceil_div((int64_t)rest, NUM_CU));
         }
         const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
         if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
