@@ -16,15 +16,27 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "mi_gemm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gemm_[a-z0-9_]+)\s*\(", text)))
+    # every identifier that is followed by an argument list at the start of a declaration
+    return sorted(set(re.findall(r"^(?:const\s+)?[a-z_0-9]+\s*\*?\s*([a-z][a-z0-9_]*)\s*\(", text, flags=re.M)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(mg.lib_path())
     names = _declared_functions()
-    assert {"gemm_f32", "gemm_f16", "gemm_i8", "gemm_workspace_bytes", "gemm_status_string"} <= set(names)
+    assert {"gemm_f32", "gemm_f16", "gemm_bf16", "gemm_i8", "gemm_f16_c16", "gemm_bf16_c16", "gemm_ex", "gemm_workspace_bytes",
+            "gemm_status_string", "gemm_solo", "gemm_select", "gemm_predict_us", "conv2d_im2row_f32", "im2row_f32",
+            "conv2d_im2row_workspace_bytes", "conv2d_im2row_shape", "conv2d_im2row_status_string",
+            "gemm_ex_status_string"} <= set(names)
     for n in names:
         assert hasattr(lib, n), "symbol %s is declared but not exported" % n
+
+
+def test_header_is_plain_c():
+    """The boundary is a C header: it must compile as C99 and as C++ without anything else included first."""
+    import subprocess
+    header = os.path.join(ROOT, "include", "mi_gemm.h")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header])
 
 
 def test_kernel_table():
