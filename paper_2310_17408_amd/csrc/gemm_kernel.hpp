@@ -572,30 +572,6 @@ __global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ w
     }
 }
 
-// The im2row transform written out (paper Sec. "Rectangular Matrices"): element (row, k) of the
-// matrix, row = (b, oh, ow), k = (r, s, c), is the image element the tap (r, s) of that output pixel
-// meets, or zero outside the image.  Used for geometries the fused kernels do not take.
-__global__ void __launch_bounds__(256) im2row_matrix_kernel(const float *__restrict__ image, float *__restrict__ matrix,
-                                                            int64_t rows, int64_t K, const Im2row g)
-{
-    const int64_t total = rows * K;
-    const int per_image = g.Hout * g.Wout;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = idx / K;
-        const int k = (int)(idx - row * K);
-        const int tap = k / g.Cin, c = k - tap * g.Cin;
-        const int r = tap / g.kw, s = tap - r * g.kw;
-        const int b = (int)(row / per_image), rem = (int)(row - (int64_t)b * per_image);
-        const int oh = rem / g.Wout, ow = rem - oh * g.Wout;
-        const int ih = oh * g.stride_h - g.pad_h + r, iw = ow * g.stride_w - g.pad_w + s;
-        float v = 0.0f;
-        if ((uint32_t)ih < (uint32_t)g.H && (uint32_t)iw < (uint32_t)g.W)
-            v = image[(((int64_t)b * g.H + ih) * g.W + iw) * g.Cin + c];
-        matrix[idx] = v;
-    }
-}
-
 // C <- beta*C (K == 0 or alpha == 0); beta == 0 stores zeros without reading C.
 template <class acc_t>
 __global__ void __launch_bounds__(256) scale_kernel(acc_t *__restrict__ C, int M, int N, int64_t ldc,
