@@ -1,6 +1,6 @@
 // C-ABI entry points: argument checks, quick returns, layout canonicalisation,
-// tile selection and launch.  Host code only; the kernels live in
-// gemm_table.hip.  Declarations and the full contract are in include/mi_gemm.h.
+// tile selection and launch.  Host code only; the kernels are instantiated in the
+// gemm_table*.hip files.  Declarations and the full contract are in include/mi_gemm.h.
 #include "../../include/mi_gemm.h"
 #include "gemm_table.h"
 
