@@ -297,7 +297,7 @@ thread_local int t_conv_path = 0;
 int g_conv_forced_path = 0;
 // forming the matrix, measured: about 5 us plus its bytes at 1.35 TB/s (a launch, one element per thread)
 constexpr double kIm2rowFixedUs = 5.0, kIm2rowBytesPerUs = 1.35e6;
-constexpr double kIm2rowLdsFactor = 1.4, kIm2rowRegFactor = 1.08;
+constexpr double kIm2rowLdsFactor = 1.32, kIm2rowRegFactor = 1.08;
 
 // 0, or -k for the k-th argument of conv2d_im2row_f32 (Cout is not checked when it is 0: im2row_f32)
 int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw, int64_t stride_h,
