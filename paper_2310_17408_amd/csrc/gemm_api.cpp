@@ -61,7 +61,21 @@ constexpr double kLaunchUs = 2.5, kReduceLaunchUs = 3.0;
 constexpr int kMaxAutoSplit = 16;
 constexpr int NUM_SIMD = 4 * NUM_CU;
 
-double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split, bool aligned = true)
+// How much longer a K step of a staged fp32 kernel takes when B has N contiguous (its tile goes through
+// the register transposes and, with bank conflicts, into LDS), alone or together with a K-contiguous A:
+// measured at 1024^3 ... 4096^3, the smaller the tile the more.  1 for every other kernel, data type and
+// orientation (the 16- and 8-bit types have direct kernels for these orientations).
+double staged_orientation_factor(int dtype, const KernelInfo *ki, bool a_kc, bool b_nc)
+{
+    if (dtype != MI_GEMM_F32 || !b_nc || !ki->transposed_ok) return 1.0;
+    const int area = ki->BM * ki->BN;
+    if (area <= 64 * 64) return a_kc ? 1.85 : 2.6;
+    if (area <= 128 * 128) return a_kc ? 1.45 : 1.9;
+    return a_kc ? 1.15 : 1.45;
+}
+
+double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split, bool aligned = true,
+                  double step_factor = 1.0)
 {
     static const int es[NUM_DTYPES] = {4, 2, 1, 2};
     const double tiles = (double)(ceil_div(M, ki->BM) * ceil_div(N, ki->BN));
@@ -88,8 +102,8 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
     } else {
         const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
         const double wgs = tiles * split;
-        const double mfma_step = 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
-        double floor_us = ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs;
+        const double mfma_step = step_factor * 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
+        double floor_us = step_factor * (ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs);
         if (M < ki->BM || N < ki->BN) floor_us *= kGuardedStepFactor;
         // time of one K step on a CU that runs `resident` workgroups side by side
         auto step_us = [&](double resident) {
@@ -117,13 +131,14 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
 }
 
 // Best split for one configuration (used directly when the configuration is forced).
-int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split, bool aligned = true)
+int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split, bool aligned = true,
+               double step_factor = 1.0)
 {
     const int64_t ktiles = ceil_div(K, ki->BK);
     int best = 1;
-    double best_us = predict_us(dtype, ki, M, N, K, 1, aligned);
+    double best_us = predict_us(dtype, ki, M, N, K, 1, aligned, step_factor);
     for (int s = 2; s <= kMaxAutoSplit && s <= max_split && 2 * s <= ktiles; ++s) {
-        const double t = predict_us(dtype, ki, M, N, K, s, aligned);
+        const double t = predict_us(dtype, ki, M, N, K, s, aligned, step_factor);
         if (t < best_us * 0.92) { best_us = t; best = s; }     // a split must pay for itself clearly
     }
     return best;
@@ -156,8 +171,9 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
                                            : ki->transposed_ok != 0;
         if (!takes) continue;
         if (!can_address(ki, lda, ldb)) continue;
-        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned);
-        const double t = predict_us(dtype, ki, M, N, K, s, aligned);
+        const double f = staged_orientation_factor(dtype, ki, a_kc, b_nc);
+        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned, f);
+        const double t = predict_us(dtype, ki, M, N, K, s, aligned, f);
         if (best < 0 || t < best_us) { best = id; best_us = t; }
     }
     return best < 0 ? 0 : best;
@@ -179,7 +195,7 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
-    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned);
+    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned, staged_orientation_factor(dtype, ki, a_kc, b_nc));
     if (s > ktiles) s = ktiles;
     if (s > fit) s = fit;
     if (s < 1) s = 1;
