@@ -11,11 +11,13 @@
  * waves of a workgroup and their MFMA blocks, and the micro-kernel (L6) is a
  * chain of MFMA instructions on accumulators held in registers.
  *
- * Common conventions for the three entry points
- * ---------------------------------------------
+ * Common conventions for the GEMM entry points (gemm_f32, gemm_f16, gemm_bf16,
+ * gemm_i8, gemm_f16_c16, gemm_bf16_c16; gemm_ex adds transposed operands, the
+ * convolution calls further down state their own arguments)
+ * --------------------------------------------------------------------------
  * layout   MI_GEMM_COL_MAJOR: X(i,j) is X[i + j*ldx];  MI_GEMM_ROW_MAJOR:
- *          X(i,j) is X[i*ldx + j].  One layout applies to A, B and C.  There
- *          are no transpose flags.
+ *          X(i,j) is X[i*ldx + j].  One layout applies to A, B and C.  Only
+ *          gemm_ex has transpose flags.
  * M, N, K  >= 0.  M == 0 or N == 0: nothing is touched.  K == 0 or alpha == 0:
  *          C <- beta*C and A, B are never read.
  * A, B, C  DEVICE pointers owned by the caller; A and B are only read, C is
