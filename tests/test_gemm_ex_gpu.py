@@ -7,7 +7,7 @@ import torch
 import oracle
 import workloads as wl
 import paper_2310_17408_amd as mg
-from gpu_case import DT, LAYOUT, TOL, max_abs, to_device
+from gpu_case import DT, LAYOUT, TIGHT, TOL, max_abs, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,7 @@ def _case(dtype, layout, ta, tb, M, N, K, alpha, beta, seed, pad=(0, 0, 0), kern
         err = oracle.normalised_error(got, ref, K, max_abs(dtype, layout, A, ar, ac) or 1.0,
                                       max_abs(dtype, layout, B, br, bc) or 1.0)
         assert err <= TOL[dtype], "%s: normalised error %.3e" % (what, err)
+        assert err <= TIGHT[dtype], "%s: normalised error %.3e above the internal bound" % (what, err)
     mask = np.ones(out.shape, dtype=bool)
     wl.logical(layout, mask, M, N)[...] = False
     assert np.array_equal(out[mask], np.asarray(C)[mask]), what + ": padding of C was overwritten"
