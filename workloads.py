@@ -11,8 +11,8 @@ Value recipes (one per configuration family):
   * int8: i.i.d. uniform integers on [-128, 127].
 The matrices stand in for the paper's workloads: a square GEMM (Sec. "Squared
 Matrices") and the GEMMs that the im2row transform produces from the
-convolution layers of ResNet50 v1.5 and VGG16 at batch 1 (Tables "Dimensions
-of the GEMM resulting from applying the im2row transform ..."), where the
+convolution layers of ResNet50 v1.5 and VGG16 at batch 1 (Tables "resnet50" and "vgg16"),
+where the
 lowered activation matrix is replaced by an i.i.d. matrix of the same shape.
 """
 import numpy as np
