@@ -136,6 +136,25 @@ int gemm_ex(int dtype, int layout, int transa, int transb, int64_t M, int64_t N,
             void *workspace, size_t workspace_bytes, void *stream);
 const char *gemm_ex_status_string(int status);
 
+/* gemm_ex for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation): the same operation, arguments
+ * (without workspace and workspace_bytes; stream is the 16th) and status codes, and bit-for-bit the
+ * result of gemm_ex with a workspace of gemm_workspace_bytes(dtype, M, N, K) bytes.  The partial tiles
+ * of a split K loop are kept in a fixed array of MI_GEMM_STATIC_WS_BYTES that is part of the library's
+ * code object (one copy per GPU, held until the process ends) instead of a caller's workspace.  The
+ * call allocates and frees nothing.  A problem whose gemm_workspace_bytes exceeds the array is
+ * rejected with MI_GEMM_STATUS_STATIC_WS_TOO_SMALL and nothing is launched (use gemm_ex with a
+ * workspace).  All calls on one GPU share that GPU's array: calls that may overlap on one GPU
+ * (different streams, or threads) race on it and must be ordered by the caller; calls on one stream
+ * are ordered.  The array keeps the last call's partial tiles; no call reads what it has not
+ * written first.  The first call on each GPU looks the array's address up and should be made outside
+ * graph capture. */
+#define MI_GEMM_STATIC_WS_BYTES (16u << 20)
+#define MI_GEMM_STATUS_STATIC_WS_TOO_SMALL (-100)
+int gemm_ex_static_ws(int dtype, int layout, int transa, int transb, int64_t M, int64_t N, int64_t K,
+                      const void *alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                      const void *beta, void *C, int64_t ldc, void *stream);
+
 /* Convolution through the im2row GEMM, fp32.  The paper's Sec. "Rectangular Matrices" takes the GEMM
  * sizes of its Tables "resnet50" and "vgg16" from the im2row transform of convolution layers
  * (m = Hout*Wout at batch 1, n = Cout, k = kh*kw*Cin) and its conclusions name convolutions as the next

@@ -57,6 +57,8 @@ def load():
     lib.gemm_kernel_tile.argtypes = [ci, ci] + [ctypes.POINTER(ci)] * 4
     lib.gemm_ex.restype = ci
     lib.gemm_ex.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64, vp, sz, vp]
+    lib.gemm_ex_static_ws.restype = ci
+    lib.gemm_ex_static_ws.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64, vp]
     lib.gemm_ex_status_string.restype = ctypes.c_char_p
     lib.gemm_ex_status_string.argtypes = [ci]
     lib.gemm_predict_us.restype = ctypes.c_double
@@ -142,6 +144,22 @@ def gemm_ex(dtype, layout, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta,
     a, b = scal(alpha), scal(beta)
     status = lib.gemm_ex(dtype, layout, int(transa), int(transb), M, N, K, ctypes.byref(a), _addr(A), lda, _addr(B), ldb,
                          ctypes.byref(b), _addr(C), ldc, ws, ws_bytes, _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, lib.gemm_ex_status_string(status).decode())
+    return status
+
+
+STATIC_WS_BYTES = 16 << 20
+STATUS_STATIC_WS_TOO_SMALL = -100
+
+
+def gemm_ex_static_ws(dtype, layout, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None, check=True):
+    """gemm_ex with the K-split scratch in the library's own fixed array (no workspace, nothing allocated)."""
+    lib = load()
+    scal = ctypes.c_int32 if dtype == I8 else ctypes.c_float
+    a, b = scal(alpha), scal(beta)
+    status = lib.gemm_ex_static_ws(dtype, layout, int(transa), int(transb), M, N, K, ctypes.byref(a), _addr(A), lda, _addr(B),
+                                   ldb, ctypes.byref(b), _addr(C), ldc, _stream(stream))
     if check and status != 0:
         raise GemmError(status, lib.gemm_ex_status_string(status).decode())
     return status

@@ -503,6 +503,9 @@ const char *gemm_status_string(int status)
 
 const char *gemm_ex_status_string(int status)
 {
+    if (status == MI_GEMM_STATUS_STATIC_WS_TOO_SMALL)
+        return "gemm_ex_static_ws: the K split of this problem needs more scratch than the library's fixed array "
+               "holds; use gemm_ex with a workspace";
     if (status == -1) return "argument 1 (dtype) is not MI_GEMM_F32, MI_GEMM_F16, MI_GEMM_I8 or MI_GEMM_BF16";
     if (status == -2) return gemm_status_string(-1);
     if (status == -3) return "argument 3 (transa) is not 0 or 1";

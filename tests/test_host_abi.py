@@ -195,3 +195,17 @@ def test_conv_geometry_and_argument_errors():
     assert mg.im2row_f32(1, 8, 8, 16, 0, 3, 1, 1, 1, 1, 1 << 20, 1 << 20, check=False) == -5
     with pytest.raises(mg.GemmError):
         mg.conv2d_im2row_force_path(3)
+
+
+def test_static_workspace_entry_point_rejects_what_does_not_fit():
+    lib = mg.load()
+    M = N = 2048
+    K = 65536
+    assert mg.gemm_workspace_bytes(mg.F16, M, N, K) > mg.STATIC_WS_BYTES
+    one, zero = ctypes.c_float(1.0), ctypes.c_float(0.0)
+    P = 0x1000      # never dereferenced: the call returns before any HIP call
+    rc = lib.gemm_ex_static_ws(mg.F16, mg.COL_MAJOR, 0, 0, M, N, K, ctypes.byref(one), P, M, P, K, ctypes.byref(zero), P, M, None)
+    assert rc == mg.STATUS_STATIC_WS_TOO_SMALL
+    # argument errors are those of gemm_ex, in the same positions
+    assert lib.gemm_ex_static_ws(9, mg.COL_MAJOR, 0, 0, 8, 8, 8, ctypes.byref(one), P, 8, P, 8, ctypes.byref(zero), P, 8, None) == -1
+    assert lib.gemm_ex_static_ws(mg.F32, mg.COL_MAJOR, 0, 0, 8, 8, 8, ctypes.byref(one), P, 7, P, 8, ctypes.byref(zero), P, 8, None) == -10
