@@ -197,7 +197,7 @@ int im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t kh, int
                int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
                const float *image, float *matrix, void *stream);
 
-/* For tests and reports: restrict later conv2d_im2row_f32 calls of this process to one path
+/* For tests and reports: restrict later conv2d_im2row_f32 calls of the calling thread to one path
  * (0 automatic, 1 in place when the geometry allows it, 2 through the im2row matrix); which path the
  * last call on this thread took (0 none, 1 in place, 2 through the matrix).  gemm_force_kernel(F32, ...)
  * and gemm_last_kernel_id / gemm_last_split apply to the GEMM inside. */
@@ -217,7 +217,8 @@ const char *gemm_status_string(int status);
  * the paper's terms, Sec. "Edge Cases"), numbered from 0.
  * gemm_kernel_name() returns a static string such as "f32_128x128_w64x64".
  * gemm_force_kernel(dtype, id, split) overrides the selector for later calls
- * of this process: id = -1 restores automatic selection; split <= 0 lets the
+ * made by the calling thread (other threads keep their own setting; meant for
+ * tests and tuning): id = -1 restores automatic selection; split <= 0 lets the
  * selector choose the K split, split >= 1 fixes it (clamped to what the
  * workspace allows).  Returns 0, or -1 for an unknown dtype / id.
  * gemm_last_kernel_id() / gemm_last_split() report what the most recent call
@@ -230,7 +231,9 @@ int gemm_last_kernel_id(void);
 int gemm_last_split(void);
 
 /* What a call with these arguments would launch (pure host computation, nothing
- * runs): the tile configuration and the K split chosen by the selector - or the
+ * runs; the answer for a problem is remembered per thread, so a repeated question
+ * - and the selection inside a repeated GEMM call - costs a table lookup, not an
+ * evaluation of the timing model): the tile configuration and the K split chosen by the selector - or the
  * forced ones - for a workspace of `workspace_bytes`, operands with tight leading
  * dimensions and 16-byte aligned base addresses.  Either output pointer may
  * be NULL.  Returns 0, or -1 unknown dtype, -2 unknown layout, -3/-4/-5 M/N/K

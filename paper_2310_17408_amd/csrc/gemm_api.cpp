@@ -19,7 +19,9 @@ constexpr int MAX_SPLIT = 32;    // upper limit of the K split
 
 struct Forced { int id = -1; int split = 0; };
 constexpr int NUM_DTYPES = 4;
-Forced g_forced[NUM_DTYPES];
+// the override of gemm_force_kernel belongs to the calling thread, like the last_* reports: a test or a
+// tuning run on one thread never changes what another thread's calls select
+thread_local Forced t_forced[NUM_DTYPES];
 thread_local int t_last_id = -1;
 thread_local int t_last_split = 0;
 
@@ -179,16 +181,10 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
     return best < 0 ? 0 : best;
 }
 
-Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws,
-              bool aligned, bool a_kc = false, bool b_nc = false)
+Choice choose_uncached(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t fit, bool aligned,
+                       bool a_kc, bool b_nc, const Forced f)
 {
     Choice c;
-    const Forced f = g_forced[dtype];
-    // how many partial tiles the workspace can hold
-    const unsigned __int128 per = (unsigned __int128)M * (unsigned __int128)N * 4u;
-    int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
-    if (fit > MAX_SPLIT) fit = MAX_SPLIT;
-    if (fit < 1) fit = 1;
     const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb) &&
                         (!(a_kc || b_nc) || kernel_info(dtype, f.id)->transposed_ok ||
                          ((!a_kc || kernel_info(dtype, f.id)->a_kc_ok) && (!b_nc || kernel_info(dtype, f.id)->b_nc_ok)));
@@ -202,6 +198,68 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     c.ktiles_per_split = (int)ceil_div(ktiles, s);
     c.split = (int)ceil_div(ktiles, c.ktiles_per_split);   // every slice gets at least one step
     return c;
+}
+
+// The model is evaluated once per distinct problem and thread: an inference loop repeats a handful of
+// shapes, and a GEMM of a few microseconds cannot afford ten evaluations of a timing model per call.
+// Everything the choice depends on is in the key; a leading dimension beyond what some configuration
+// can address (rare: rows 2^28 bytes apart) bypasses the table.
+struct ChoiceKey {
+    int64_t M, N, K;
+    int32_t forced_split;
+    uint32_t bits;      // dtype, aligned, a_kc, b_nc, fit, forced id + 1
+    bool operator==(const ChoiceKey &o) const
+    {
+        return M == o.M && N == o.N && K == o.K && forced_split == o.forced_split && bits == o.bits;
+    }
+};
+struct ChoiceSlot { ChoiceKey key; Choice choice; bool used; };
+constexpr int kChoiceSlots = 256;       // direct-mapped; a collision just re-evaluates
+thread_local ChoiceSlot t_choice[kChoiceSlots];
+
+// Smallest leading dimension that some configuration of the data type cannot address (INT64_MAX: none).
+int64_t smallest_ld_limit(int dtype)
+{
+    int64_t m = INT64_MAX;
+    for (int id = 0; id < kernel_count(dtype); ++id) {
+        const KernelInfo *ki = kernel_info(dtype, id);
+        if (ki->max_lda > 0 && ki->max_lda < m) m = ki->max_lda;
+        if (ki->max_ldb > 0 && ki->max_ldb < m) m = ki->max_ldb;
+    }
+    return m;
+}
+
+int64_t addressing_limit(int dtype)
+{
+    static const int64_t limit[NUM_DTYPES] = {smallest_ld_limit(0), smallest_ld_limit(1), smallest_ld_limit(2),
+                                              smallest_ld_limit(3)};
+    return limit[dtype];
+}
+
+Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws,
+              bool aligned, bool a_kc = false, bool b_nc = false)
+{
+    const Forced f = t_forced[dtype];
+    // how many partial tiles the workspace can hold
+    const unsigned __int128 per = (unsigned __int128)M * (unsigned __int128)N * 4u;
+    int64_t fit = (have_ws && per > 0) ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
+    if (fit > MAX_SPLIT) fit = MAX_SPLIT;
+    if (fit < 1) fit = 1;
+    const int64_t limit = addressing_limit(dtype);
+    if (lda > limit || ldb > limit || f.id >= 254) return choose_uncached(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc, f);
+    ChoiceKey key;
+    key.M = M; key.N = N; key.K = K;
+    key.forced_split = f.split;
+    key.bits = (uint32_t)dtype | (aligned ? 4u : 0u) | (a_kc ? 8u : 0u) | (b_nc ? 16u : 0u) | ((uint32_t)fit << 5) |
+               ((uint32_t)(f.id + 1) << 11);
+    uint64_t h = (uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^ (uint64_t)K * 0x165667B19E3779F9ull ^
+                 ((uint64_t)key.bits << 32 | (uint32_t)key.forced_split) * 0xD6E8FEB86659FD93ull;
+    ChoiceSlot &slot = t_choice[(h >> 40) % kChoiceSlots];
+    if (slot.used && slot.key == key) return slot.choice;
+    slot.choice = choose_uncached(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc, f);
+    slot.key = key;
+    slot.used = true;
+    return slot.choice;
 }
 
 bool aligned16(const void *p, int64_t ld, int es)
@@ -310,7 +368,7 @@ struct ConvGeometry {
     Im2row g;
 };
 thread_local int t_conv_path = 0;
-int g_conv_forced_path = 0;
+thread_local int t_conv_forced_path = 0;     // per thread, like the GEMM override
 // forming the matrix, measured: about 5 us plus its bytes at 1.35 TB/s (a launch, one element per thread)
 constexpr double kIm2rowFixedUs = 5.0, kIm2rowBytesPerUs = 1.35e6;
 constexpr double kIm2rowLdsFactor = 1.32, kIm2rowRegFactor = 1.08;
@@ -346,7 +404,11 @@ int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout
 bool conv_fused_ok(int64_t batch, const ConvGeometry &c)
 {
     const unsigned __int128 image_bytes = (unsigned __int128)batch * c.g.H * c.g.W * (unsigned __int128)c.g.Cin * 4u;
-    return image_bytes < ((unsigned __int128)1 << 31);
+    // the kernels also form offsets of padded positions ((W - iw)*Cin, -iw*Cin, rows above and below the
+    // image) in 32-bit integers: the padded image of one batch entry must fit them as well
+    const unsigned __int128 padded_row = (unsigned __int128)(c.g.W + 2 * (int64_t)c.g.pad_w) * (unsigned __int128)c.g.Cin;
+    const unsigned __int128 padded_image = (unsigned __int128)(c.g.H + 2 * (int64_t)c.g.pad_h) * padded_row;
+    return image_bytes < ((unsigned __int128)1 << 31) && padded_image < ((unsigned __int128)1 << 29);
 }
 
 // How configuration ki can read the im2row matrix in place: a K step inside one filter tap (Cin a multiple
@@ -367,7 +429,7 @@ int conv_fused_kernel(const ConvGeometry &c, int64_t fit, bool image_aligned, do
 {
     int best = -1;
     double best_us = 0.0;
-    const Forced f = g_forced[MI_GEMM_F32];
+    const Forced f = t_forced[MI_GEMM_F32];
     for (int id = 0; id < kernel_count(MI_GEMM_F32); ++id) {
         const KernelInfo *ki = kernel_info(MI_GEMM_F32, id);
         if (!conv_fused_launcher(ki, c, image_aligned) || !can_address(ki, c.N, 0)) continue;
@@ -469,20 +531,39 @@ size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
 {
     if (dtype < 0 || dtype >= NUM_DTYPES || M <= 0 || N <= 0 || K <= 0) return 0;
     if (M > INT_MAX || N > INT_MAX || K > INT_MAX) return 0;
-    // the largest split the model would give any configuration, in either orientation (a
-    // row-major call runs the transposed problem)
+    // callers size a workspace per call site and problem: remember the last few answers of this thread
+    struct Slot { int dtype; int64_t M, N, K; size_t bytes; bool used; };
+    constexpr int kSlots = 64;
+    thread_local Slot t_slots[kSlots];
+    Slot &slot = t_slots[((uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^
+                          (uint64_t)K * 0x165667B19E3779F9ull ^ (uint64_t)dtype) >> 40 & (kSlots - 1)];
+    if (slot.used && slot.dtype == dtype && slot.M == M && slot.N == N && slot.K == K) return slot.bytes;
+    // the largest split the model would give any configuration, in either orientation (a row-major call
+    // runs the transposed problem), for aligned and unaligned operands, and for every slowdown the model
+    // applies to transposed operands (gemm_ex on the staged fp32 kernels)
+    static const bool kOrient[4][2] = {{false, false}, {true, false}, {false, true}, {true, true}};
     int64_t smax = 1;
     for (int id = 0; id < kernel_count(dtype); ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        for (int aligned = 0; aligned < 2; ++aligned) {
-            const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT, aligned != 0);
-            const int64_t s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT, aligned != 0);
-            if (s1 > smax) smax = s1;
-            if (s2 > smax) smax = s2;
+        double seen[4];
+        int nseen = 0;
+        for (int o = 0; o < 4; ++o) {
+            const double f = staged_orientation_factor(dtype, ki, kOrient[o][0], kOrient[o][1]);
+            bool dup = false;
+            for (int j = 0; j < nseen; ++j) dup = dup || seen[j] == f;
+            if (dup) continue;
+            seen[nseen++] = f;
+            for (int aligned = 0; aligned < 2; ++aligned) {
+                const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT, aligned != 0, f);
+                const int64_t s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT, aligned != 0, f);
+                if (s1 > smax) smax = s1;
+                if (s2 > smax) smax = s2;
+            }
         }
     }
-    if (smax <= 1) return 0;
-    return (size_t)smax * (size_t)M * (size_t)N * 4u;
+    const size_t bytes = smax <= 1 ? 0 : (size_t)smax * (size_t)M * (size_t)N * 4u;
+    slot.dtype = dtype; slot.M = M; slot.N = N; slot.K = K; slot.bytes = bytes; slot.used = true;
+    return bytes;
 }
 
 const char *gemm_status_string(int status)
@@ -535,8 +616,8 @@ int gemm_force_kernel(int dtype, int id, int split)
 {
     if (dtype < 0 || dtype >= NUM_DTYPES) return -1;
     if (id < -1 || id >= kernel_count(dtype)) return -1;
-    g_forced[dtype].id = id;
-    g_forced[dtype].split = split > 0 ? split : 0;
+    t_forced[dtype].id = id;
+    t_forced[dtype].split = split > 0 ? split : 0;
     return 0;
 }
 
@@ -625,10 +706,10 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
     // explicit: the matrix in the workspace, then the GEMM with what is left of it
     const bool explicit_fits = ws_bytes >= matrix_bytes;
     bool fused = fused_id >= 0;
-    if (g_conv_forced_path == 2 || !fused) {
+    if (t_conv_forced_path == 2 || !fused) {
         if (!explicit_fits) return -18;
         fused = false;
-    } else if (g_conv_forced_path == 0 && explicit_fits && g_forced[MI_GEMM_F32].id < 0) {
+    } else if (t_conv_forced_path == 0 && explicit_fits && t_forced[MI_GEMM_F32].id < 0) {
         const int gid = auto_kernel(MI_GEMM_F32, c.N, c.M, c.K, c.N, c.K, 1, true, false, false);
         const double explicit_us = predict_us(MI_GEMM_F32, kernel_info(MI_GEMM_F32, gid), c.N, c.M, c.K, 1) + kIm2rowFixedUs +
                                    (double)matrix_bytes / kIm2rowBytesPerUs;
@@ -647,7 +728,7 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
     }
 
     const KernelInfo *ki = kernel_info(MI_GEMM_F32, fused_id);
-    const Forced f = g_forced[MI_GEMM_F32];
+    const Forced f = t_forced[MI_GEMM_F32];
     const int64_t ktiles = ceil_div(c.K, ki->BK);
     int64_t sp = f.split >= 1 ? f.split : (ki->waves_k == 0 ? 1 : auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit));
     if (sp > ktiles) sp = ktiles;
@@ -741,7 +822,7 @@ const char *conv2d_im2row_status_string(int status)
 int conv2d_im2row_force_path(int path)
 {
     if (path < 0 || path > 2) return -1;
-    g_conv_forced_path = path;
+    t_conv_forced_path = path;
     return 0;
 }
 

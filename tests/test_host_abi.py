@@ -197,6 +197,57 @@ def test_conv_geometry_and_argument_errors():
         mg.conv2d_im2row_force_path(3)
 
 
+def test_repeated_selection_is_a_table_lookup():
+    """The timing model runs once per distinct problem and thread: 10^4 repeats of gemm_select on a shape whose
+    selection weighs a dozen configurations and splits must cost well under a microsecond each beyond what the
+    foreign-function call itself costs (measured on a call of the same arity that returns at its first check)."""
+    import time
+    lib = mg.load()
+    kid, split = ctypes.c_int(-1), ctypes.c_int(0)
+    pk, ps = ctypes.byref(kid), ctypes.byref(split)
+    ws = mg.gemm_workspace_bytes(mg.F32, 49, 512, 4608)
+
+    def mean_us(dtype, reps=10000):
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            lib.gemm_select(dtype, mg.COL_MAJOR, 49, 512, 4608, ws, pk, ps)
+        return (time.perf_counter() - t0) / reps * 1e6
+
+    for dtype in (mg.F32, mg.F16, mg.I8):
+        assert lib.gemm_select(dtype, mg.COL_MAJOR, 49, 512, 4608, ws, pk, ps) == 0      # the first call fills the table
+        first = (kid.value, split.value)
+        floor = min(mean_us(99) for _ in range(3))             # unknown dtype: returns -1 at once
+        cached = min(mean_us(dtype) for _ in range(3))
+        assert (kid.value, split.value) == first
+        assert cached - floor < 0.5, "selection costs %.2f us per call beyond the call itself (%.2f)" % (cached - floor, floor)
+    # the table is keyed on everything the choice depends on: another workspace size, a forced configuration
+    # and a forced split each get their own answer, and the first answer comes back afterwards
+    base = mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, ws)
+    assert mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, 0)[1] == 1
+    mg.gemm_force_kernel(mg.F32, 0, 3)
+    try:
+        assert mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, ws) == (0, 3)
+    finally:
+        mg.gemm_force_kernel(mg.F32, -1, 0)
+    assert mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, ws) == base
+    assert mg.gemm_select(mg.F32, mg.ROW_MAJOR, 512, 49, 4608, ws) == base           # the same canonical problem
+
+
+def test_force_kernel_is_per_thread():
+    import threading
+    seen = {}
+    mg.gemm_force_kernel(mg.F32, 0, 2)
+    try:
+        t = threading.Thread(target=lambda: seen.setdefault("other", mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, 1 << 22)))
+        t.start()
+        t.join()
+        seen["mine"] = mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, 1 << 22)
+    finally:
+        mg.gemm_force_kernel(mg.F32, -1, 0)
+    assert seen["mine"] == (0, 2)
+    assert seen["other"] == mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, 1 << 22) != (0, 2)
+
+
 def test_static_workspace_entry_point_rejects_what_does_not_fit():
     lib = mg.load()
     M = N = 2048
