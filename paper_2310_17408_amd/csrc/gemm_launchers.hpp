@@ -4,6 +4,7 @@
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
+#include "gemm_kernel_ring.hpp"
 #include "gemm_kernel_reg32.hpp"
 #include "gemm_kernel_reg16.hpp"
 #include "gemm_solo.hpp"
@@ -126,6 +127,50 @@ static constexpr KernelInfo info_dma16(const char *name, int prio, int eff_pct, 
 {
     KernelInfo k = info_dma<T, DmaMicro16<T>>(name, prio, eff_pct, floor_ns, setup_ns);
     k.launch = &launch_tile_dma16<T>;
+    k.a_kc_ok = 1;
+    k.b_nc_ok = (T::BM == T::BN) ? 1 : 0;
+    return k;
+}
+
+// the ring kernel in one operand orientation (as launch_dma16_variant)
+template <class T, bool A_KC, bool B_NC>
+static hipError_t launch_ring_variant(const Params &p, hipStream_t stream)
+{
+    static bool attr_done[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_ring<T, A_KC, B_NC>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL((gemm_kernel_ring<T, A_KC, B_NC>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+template <class T>
+static hipError_t launch_tile_ring(const Params &p, hipStream_t stream)
+{
+    if constexpr (T::BM == T::BN) {
+        if (p.b_nc) return p.a_kc ? launch_ring_variant<T, true, true>(p, stream) : launch_ring_variant<T, false, true>(p, stream);
+    } else {
+        if (p.b_nc) return hipErrorInvalidValue;        // the selector never asks for it (b_nc_ok == 0)
+    }
+    return p.a_kc ? launch_ring_variant<T, true, false>(p, stream) : launch_ring_variant<T, false, false>(p, stream);
+}
+template <class T>
+static hipError_t solo_ring(int wg, int ks, int fill, hipStream_t st)
+{
+    return launch_solo<T>(&solo_kernel_ring<T>, wg, ks, fill, st);
+}
+template <class T>
+static constexpr KernelInfo info_ring(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
+{
+    KernelInfo k = info_dma<T, DmaMicro16<T>>(name, prio, eff_pct, floor_ns, setup_ns);
+    k.launch = &launch_tile_ring<T>;
+    k.solo = &solo_ring<T>;
     k.a_kc_ok = 1;
     k.b_nc_ok = (T::BM == T::BN) ? 1 : 0;
     return k;

@@ -9,6 +9,7 @@
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
+#include "gemm_kernel_ring.hpp"
 #include "gemm_kernel_reg32.hpp"
 #include "gemm_kernel_reg16.hpp"
 
@@ -133,6 +134,42 @@ __global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_micro(int ksteps, 
             micro.load(smem, (s + 1) % Micro::STEPS);
             micro.mma(s, acc);
             __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    solo_finish(acc);
+}
+
+// ring kernels (gemm_kernel_ring.hpp): the two halves of a stage with the fragment reads of the next half
+// under them, two passes per iteration so that the register sets alternate as in the GEMM's K loop
+template <class T>
+__global__ void __launch_bounds__(T::NT, T::MINB) solo_kernel_ring(int ksteps, int fill)
+{
+    typedef RingMicro16<T> Micro;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    solo_fill<T::DT::ES, T::NT>(smem, T::STAGE, fill);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm0 = (wave % T::WAVES_M) * T::WM, wn0 = (wave / T::WAVES_M) * T::WN;
+    Micro micro;
+    micro.init(lane, wm0, wn0);
+    typename Micro::accv acc[Micro::TM][Micro::TN];
+#pragma unroll
+    for (int i = 0; i < Micro::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Micro::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0;
+    micro.load_a(smem, 0);
+    micro.load_b(smem, 0);
+    for (int it = 0; it < ksteps; it += 2) {
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+            micro.load_a(smem, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            micro.mma_half(0, par, acc, [](int) {});
+            micro.load_a(smem, 0);
+            micro.load_b(smem, par ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+            micro.mma_half(1, par, acc, [](int) {});
         }
     }
     solo_finish(acc);

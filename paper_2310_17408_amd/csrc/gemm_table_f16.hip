@@ -13,12 +13,14 @@ static const KernelInfo k_f16[] = {
     info<F16_64x64>("f16_64x64_w32x32", 1, 30, 700, 1500),
     info_dma<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma", 0, 72, 880, 1500),
     info_dma<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma", 0, 82, 1800, 1500),
-    info_dma16<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma16", 1, 87, 1700, 3000),
+    info_dma16<DmaTile<F16, 256, 256, 2, 4, 4, 2, 1>>("f16_256x256_w128x64_dma16", 0, 87, 1700, 3000),
     info_dma16<DmaTile<F16, 128, 128, 2, 2, 4, 2, 2>>("f16_128x128_w64x64_dma16", 1, 75, 850, 3000),
     info_reg16<Reg16Tile<F16, 2, 2, 2, 1, 4, 3>>("f16_64x64_w32x32_reg", 1, 20, 300, 1200, 1, 12.5e6),
     info_reg16<Reg16Tile<F16, 2, 1, 1, 4, 4, 3>>("f16_32x32_k4_reg", 1, 20, 350, 900, 1, 11.0e6),
     info_dma16<DmaTile<F16, 128, 64, 2, 2, 4, 2, 3>>("f16_128x64_w64x32_dma16", 1, 55, 400, 3000),
     info_reg16<Reg16Tile<F16, 1, 1, 1, 4, 4, 4>>("f16_32x16_k4_reg", 1, 20, 250, 900, 1, 11.0e6),
+    info_ring<DmaTile<F16, 256, 256, 2, 4, 2, 4, 1>>("f16_256x256_w128x64_ring", 1, 88, 740, 3000),
+    info_ring<DmaTile<F16, 128, 128, 2, 4, 2, 4, 2>>("f16_128x128_w64x32_ring", 1, 75, 310, 3000),
 };
 const KernelInfo *kernel_table_f16(int *count)
 {

@@ -12,6 +12,7 @@ from gpu_case import DT, LAYOUT, TIGHT, TOL, max_abs, to_device
 pytestmark = pytest.mark.gpu
 
 GEN = {"f32": wl.uniform_f32, "f16": wl.normal_f16_bits, "bf16": wl.normal_bf16_bits, "i8": wl.uniform_i8}
+DIRECT = ("_dma16", "_ring")       # the direct-to-LDS kernels with 16 x 16 MFMA blocks: two stages, or a ring of four
 SMALL = {"f32": wl.small_int_f32, "f16": wl.small_int_f16_bits, "bf16": wl.small_int_bf16_bits}
 
 
@@ -117,7 +118,7 @@ def test_k_contiguous_a_on_the_direct_kernels(dtype):
     direct-to-LDS kernels stage A like B.  Aligned multi-tile shapes (transfers only), shapes whose last tile
     is moved back, odd leading dimensions (guarded staging) and a K split, on every such kernel; and the
     automatic choice must be one of them for a large problem."""
-    direct = [i for i in range(mg.gemm_kernel_count(DT[dtype])) if mg.gemm_kernel_name(DT[dtype], i).endswith("_dma16")]
+    direct = [i for i in range(mg.gemm_kernel_count(DT[dtype])) if mg.gemm_kernel_name(DT[dtype], i).endswith(DIRECT)]
     assert len(direct) >= 3
     a, b = (3, -2) if dtype == "i8" else (1.5, 0.5)
     for kid in direct:
@@ -130,7 +131,7 @@ def test_k_contiguous_a_on_the_direct_kernels(dtype):
         k, s = _case(dtype, "row", 0, 1, 256, 256, 2048, a, b, seed=7640 + kid, kernel_id=kid, split=4)
         assert (k, s) == (kid, 4)
     k, _ = _case(dtype, "row", 0, 1, 2048, 2048, 1024, 1, 0, seed=7650)
-    assert mg.gemm_kernel_name(DT[dtype], k).endswith("_dma16")
+    assert mg.gemm_kernel_name(DT[dtype], k).endswith(DIRECT)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
@@ -138,7 +139,7 @@ def test_n_contiguous_b_on_the_square_direct_kernels(dtype):
     """op(B) = B^T in column-major terms (B with N contiguous), alone and together with a K-contiguous A: the
     direct kernels with square tiles stage B like the canonical A (transposing LDS reads)."""
     square = [i for i in range(mg.gemm_kernel_count(DT[dtype]))
-              if mg.gemm_kernel_name(DT[dtype], i).endswith("_dma16") and mg.gemm_kernel_tile(DT[dtype], i)[0] == mg.gemm_kernel_tile(DT[dtype], i)[1]]
+              if mg.gemm_kernel_name(DT[dtype], i).endswith(DIRECT) and mg.gemm_kernel_tile(DT[dtype], i)[0] == mg.gemm_kernel_tile(DT[dtype], i)[1]]
     assert len(square) >= 2
     a, b = (3, -2) if dtype == "i8" else (1.5, 0.5)
     for kid in square:
@@ -157,4 +158,4 @@ def test_n_contiguous_b_on_the_square_direct_kernels(dtype):
     assert k != odd[0]
     for ta in (0, 1):
         k, _ = _case(dtype, "col", ta, 1, 2048, 2048, 1024, 1, 0, seed=7790 + ta)
-        assert mg.gemm_kernel_name(DT[dtype], k).endswith("_dma16")
+        assert mg.gemm_kernel_name(DT[dtype], k).endswith(DIRECT)

@@ -82,3 +82,4 @@ def test_transposed_operands_hot_loop_exact(dtype, ta, tb):
         names = {mg.gemm_kernel_name(DT[dtype], k) for k in ran}
         if dtype != "f32":
             assert any(n.endswith("256x256_w128x64_dma16") for n in names), names
+            assert any(n.endswith("256x256_w128x64_ring") for n in names), names
