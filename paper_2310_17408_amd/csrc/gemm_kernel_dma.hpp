@@ -38,6 +38,16 @@ struct DmaTile {
     static constexpr int B_ROWB = 32 * KSTEPS;          // bytes of one row of the B tile
     static constexpr int B_CPR = 2 * KSTEPS;            // 16-byte chunks per B row
     static constexpr int B_RP256 = 16 / B_CPR;          // B rows per 256 bytes (one pass over the LDS banks)
+    // Chunk swizzle of a K-contiguous tile row: chunk c of row n is stored at c ^ b_swz(n), so that the 16-byte
+    // fragment reads of a wave (lane l: row l%16, chunk l/16 of a K step) meet no bank twice.  Rows of 128 bytes:
+    // the row pair takes the 3 chunk bits; rows of 64 bytes (4 chunks, 4 rows per pass over the banks): the
+    // second of two groups of 4 rows swaps its chunk pairs (found by measuring all linear maps of the row
+    // index with SQ_LDS_BANK_CONFLICT: (n / 4) % 4, the analogue of the wider rows, conflicts two-way).
+    static __host__ __device__ constexpr int b_swz(int n)
+    {
+        return B_CPR == 8 ? ((n / 2) % 8) : (((n >> 2) & 1) << 1);
+    }
+    static constexpr int B_SWZ_PERIOD = 16;             // b_swz(n + 16) == b_swz(n)
     static constexpr int A_ROWB = BM * ES;              // bytes of one k-row of the A tile
     static constexpr int A_CPR = A_ROWB / 16;           // 16-byte chunks per k-row
     static constexpr int A_BYTES = BK * A_ROWB;

@@ -47,7 +47,7 @@ struct RingMicro16 {
     __device__ __forceinline__ void init(int lane, int wm0, int wn0)
     {
         const int r = lane & 15, g = lane >> 4;
-        const int x = (r / T::B_RP256) % T::B_CPR;      // swizzle of a K-contiguous tile row
+        const int x = T::b_swz(r);                      // swizzle of a K-contiguous tile row (period 16 rows)
         const int kr = r / T::LPR, ml = r % T::LPR;     // transposing read: k-row and 8-byte piece of the lane
         if constexpr (B_NC) {
 #pragma unroll
@@ -151,11 +151,11 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_ring(const Params 
     const int a_row_in = A_KC ? lane / T::B_CPR : lane / A_CPR, a_pch = A_KC ? lane % T::B_CPR : lane % A_CPR;
     const int b_row_in = B_NC ? lane / A_CPR : lane / T::B_CPR, b_pch = B_NC ? lane % A_CPR : lane % T::B_CPR;
     static_assert((NW * T::A_ROWS_PER_INST) % T::SWZ_PERIOD == 0, "A swizzle must repeat every NW blocks");
-    static_assert((NW * T::B_ROWS_PER_INST) % (T::B_RP256 * T::B_CPR) == 0, "B swizzle must repeat every NW blocks");
-    const int a_ch = A_KC ? a_pch ^ (((wave * T::B_ROWS_PER_INST + a_row_in) / T::B_RP256) % T::B_CPR)
+    static_assert((NW * T::B_ROWS_PER_INST) % T::B_SWZ_PERIOD == 0, "B swizzle must repeat every NW blocks");
+    const int a_ch = A_KC ? a_pch ^ T::b_swz(wave * T::B_ROWS_PER_INST + a_row_in)
                           : a_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + a_row_in);
     const int b_ch = B_NC ? b_pch ^ T::a_swz(wave * T::A_ROWS_PER_INST + b_row_in)
-                          : b_pch ^ (((wave * T::B_ROWS_PER_INST + b_row_in) / T::B_RP256) % T::B_CPR);
+                          : b_pch ^ T::b_swz(wave * T::B_ROWS_PER_INST + b_row_in);
     const uint32_t a_lane_off = (uint32_t)(((int64_t)a_row_in * p.lda + a_ch * KCH) * ES);
     const uint32_t b_lane_off = (uint32_t)(((int64_t)b_row_in * p.ldb + b_ch * KCH) * ES);
     constexpr int A_RPI = A_KC ? T::B_ROWS_PER_INST : T::A_ROWS_PER_INST;          // tile rows (m or k) per transfer
