@@ -26,6 +26,8 @@ from .ref import (  # noqa: F401
     conv_output_shape,
     im2row_f32,
     conv2d_nhwc_f32,
+    im2row,
+    conv2d_nhwc,
     narrow_f16,
     narrow_bf16,
     half_bits_to_double,

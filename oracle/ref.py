@@ -58,6 +58,10 @@ def _load():
             getattr(lib, name).argtypes = [vp, vp, i64]
         lib.ref_im2row_f32.restype = ctypes.c_int
         lib.ref_im2row_f32.argtypes = [i64] * 10 + [vp, vp]
+        lib.ref_im2row_ex.restype = ctypes.c_int
+        lib.ref_im2row_ex.argtypes = [ctypes.c_int] + [i64] * 10 + [vp, vp]
+        lib.ref_conv2d_nhwc_ex.restype = ctypes.c_int
+        lib.ref_conv2d_nhwc_ex.argtypes = [ctypes.c_int] + [i64] * 11 + [dbl, vp, vp, dbl, vp, vp]
         lib.ref_conv2d_nhwc_f32.restype = ctypes.c_int
         lib.ref_conv2d_nhwc_f32.argtypes = [i64] * 11 + [f32, vp, vp, f32, vp, vp]
         _lib = lib
@@ -211,6 +215,48 @@ def conv2d_nhwc_f32(x, w, stride, pad, alpha=1.0, beta=0.0, y_old=None):
     out = np.zeros((batch, Hout, Wout, Cout), dtype=np.float64)
     rc = _load().ref_conv2d_nhwc_f32(batch, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1],
                                      alpha, _ptr(x), _ptr(w), beta, _ptr(y_old), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    return out
+
+
+_CODE = {"f32": 0, "f16": 1, "i8": 2, "bf16": 3}
+_IN_DTYPE = {"f32": np.float32, "f16": np.uint16, "bf16": np.uint16, "i8": np.int8}
+
+
+def im2row(dtype, x, kh, kw, stride, pad):
+    """The im2row matrix of a channels-last tensor x[batch, H, W, Cin] of any of the data types ("f32", "f16" and
+    "bf16" as uint16 bit patterns, "i8"), in the same type."""
+    x = np.ascontiguousarray(x, dtype=_IN_DTYPE[dtype])
+    batch, H, W, Cin = x.shape
+    Hout, Wout = conv_output_shape(H, W, kh, kw, stride, pad)
+    out = np.zeros((batch * Hout * Wout, kh * kw * Cin), dtype=_IN_DTYPE[dtype])
+    rc = _load().ref_im2row_ex(_CODE[dtype], batch, H, W, Cin, kh, kw, stride[0], stride[1], pad[0], pad[1], _ptr(x), _ptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle returned %d" % rc)
+    return out
+
+
+def conv2d_nhwc(dtype, x, w, stride, pad, alpha=1, beta=0, y_old=None):
+    """alpha * conv(x[batch,H,W,Cin], w[kh,kw,Cin,Cout]) + beta * y_old for inputs of any data type; y_old is float32
+    (int32 for "i8"); returns float64 (int64 for "i8") [batch,Hout,Wout,Cout]."""
+    x = np.ascontiguousarray(x, dtype=_IN_DTYPE[dtype])
+    w = np.ascontiguousarray(w, dtype=_IN_DTYPE[dtype])
+    batch, H, W, Cin = x.shape
+    kh, kw, cin2, Cout = w.shape
+    if cin2 != Cin:
+        raise ValueError("filter and input disagree on Cin")
+    Hout, Wout = conv_output_shape(H, W, kh, kw, stride, pad)
+    if y_old is None:
+        if beta != 0:
+            raise ValueError("beta != 0 needs y_old")
+    else:
+        y_old = np.ascontiguousarray(y_old, dtype=np.int32 if dtype == "i8" else np.float32)
+        if y_old.shape != (batch, Hout, Wout, Cout):
+            raise ValueError("y_old has the wrong shape")
+    out = np.zeros((batch, Hout, Wout, Cout), dtype=np.int64 if dtype == "i8" else np.float64)
+    rc = _load().ref_conv2d_nhwc_ex(_CODE[dtype], batch, H, W, Cin, Cout, kh, kw, stride[0], stride[1], pad[0], pad[1],
+                                    float(alpha), _ptr(x), _ptr(w), float(beta), _ptr(y_old), _ptr(out))
     if rc != 0:
         raise RuntimeError("oracle returned %d" % rc)
     return out

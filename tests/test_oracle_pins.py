@@ -565,6 +565,105 @@ def test_conv_is_the_gemm_of_the_im2row_matrix_and_matches_torch():
             assert np.array_equal(A, x.reshape(M, K))
 
 
+# ------------------------------------------------------------ the same for binary16, bfloat16 and int8 inputs
+def _to_type(dtype, x):
+    """Small-integer or otherwise exactly representable float values as arrays of the oracle's input type."""
+    x = np.asarray(x, dtype=np.float64)
+    if dtype == "f32":
+        return x.astype(np.float32)
+    if dtype == "f16":
+        return x.astype(np.float16).view(np.uint16)
+    if dtype == "bf16":
+        return (x.astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)     # exact for these values
+    return x.astype(np.int8)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8"])
+def test_typed_conv_worked_examples_by_hand(dtype):
+    """The 3 x 3 example worked out in test_conv_worked_examples_by_hand, in every input type (its values
+    are small integers, which all of them hold exactly)."""
+    x = _to_type(dtype, np.arange(9).reshape(1, 3, 3, 1))
+    w = _to_type(dtype, np.array([[1, 2], [3, 4]]).reshape(2, 2, 1, 1))
+    assert np.array_equal(oracle.conv2d_nhwc(dtype, x, w, (1, 1), (0, 0))[0, :, :, 0], [[27, 37], [57, 67]])
+    assert np.array_equal(oracle.conv2d_nhwc(dtype, x, w, (2, 2), (1, 1))[0, :, :, 0], [[0, 11], [30, 67]])
+    assert np.array_equal(oracle.im2row(dtype, x, 2, 2, (1, 1), (0, 0)),
+                          _to_type(dtype, [[0, 1, 3, 4], [1, 2, 4, 5], [3, 4, 6, 7], [4, 5, 7, 8]]))
+    old = np.full((1, 2, 2, 1), 10, dtype=np.int32 if dtype == "i8" else np.float32)
+    assert np.array_equal(oracle.conv2d_nhwc(dtype, x, w, (1, 1), (0, 0), 2, -1, old)[0, :, :, 0], [[44, 64], [104, 124]])
+    if dtype != "i8":
+        bad = np.full((1, 2, 2, 1), np.nan, dtype=np.float32)       # beta == 0 does not read the old output
+        assert np.array_equal(oracle.conv2d_nhwc(dtype, x, w, (1, 1), (0, 0), 1, 0, bad)[0, :, :, 0], [[27, 37], [57, 67]])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("stride,pad", [((1, 1), (0, 0)), ((2, 1), (1, 2)), ((3, 2), (2, 0))])
+def test_typed_conv_single_one_input_returns_the_filter(dtype, stride, pad):
+    H, W, Cin, Cout, kh, kw = 7, 6, 3, 4, 3, 2
+    rng = np.random.default_rng(79)
+    wv = rng.integers(-100, 101, size=(kh, kw, Cin, Cout)).astype(np.float64)      # exact in all three types
+    w = _to_type(dtype, wv)
+    Hout, Wout = oracle.conv_output_shape(H, W, kh, kw, stride, pad)
+    for (i0, j0, c0) in ((0, 0, 0), (3, 2, 1), (6, 5, 2)):
+        xv = np.zeros((1, H, W, Cin))
+        xv[0, i0, j0, c0] = 1
+        got = oracle.conv2d_nhwc(dtype, _to_type(dtype, xv), w, stride, pad)
+        want = np.zeros((1, Hout, Wout, Cout))
+        for oh in range(Hout):
+            for ow in range(Wout):
+                r, s = i0 - oh * stride[0] + pad[0], j0 - ow * stride[1] + pad[1]
+                if 0 <= r < kh and 0 <= s < kw:
+                    want[0, oh, ow] = wv[r, s, c0]
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_typed_conv_all_ones_counts_the_taps_inside_the_image(dtype):
+    H, W, Cin, Cout, kh, kw, stride, pad = 6, 5, 4, 2, 3, 3, (1, 2), (1, 1)
+    got = oracle.conv2d_nhwc(dtype, _to_type(dtype, np.ones((2, H, W, Cin))), _to_type(dtype, np.ones((kh, kw, Cin, Cout))), stride, pad)
+    Hout, Wout = oracle.conv_output_shape(H, W, kh, kw, stride, pad)
+    for oh in range(Hout):
+        for ow in range(Wout):
+            rows = sum(1 for r in range(kh) if 0 <= oh * stride[0] - pad[0] + r < H)
+            cols = sum(1 for s in range(kw) if 0 <= ow * stride[1] - pad[1] + s < W)
+            assert np.all(got[:, oh, ow, :] == rows * cols * Cin)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8"])
+def test_typed_conv_is_the_gemm_of_the_im2row_matrix_and_matches_torch(dtype):
+    """conv == the (pinned) GEMM oracle of the same type on the im2row matrix, the typed transform == the fp32
+    transform on the decoded values, and torch's convolution in float64 on the decoded values."""
+    gen = {"f32": wl.uniform_f32, "f16": wl.normal_f16_bits, "bf16": wl.normal_bf16_bits, "i8": wl.uniform_i8}[dtype]
+    gemm = {"f32": oracle.gemm_f32, "f16": oracle.gemm_f16, "bf16": oracle.gemm_bf16, "i8": oracle.gemm_i8}[dtype]
+    decode = {"f32": lambda b: b.astype(np.float64), "f16": oracle.half_bits_to_double, "bf16": oracle.bfloat16_bits_to_double,
+              "i8": lambda b: b.astype(np.float64)}[dtype]
+    rng = np.random.default_rng(80)
+    for idx, (batch, H, W, Cin, Cout, kh, kw, stride, pad) in enumerate(((2, 9, 8, 5, 7, 3, 3, (1, 1), (1, 1)), (1, 11, 13, 16, 6, 5, 2, (2, 3), (2, 1)),
+                                                                         (3, 6, 6, 8, 8, 1, 1, (1, 1), (0, 0)), (1, 8, 8, 4, 3, 3, 3, (2, 2), (0, 0)))):
+        x = gen(8100 + idx, "row", batch * H * W, Cin).reshape(batch, H, W, Cin)
+        w = gen(8200 + idx, "row", kh * kw * Cin, Cout).reshape(kh, kw, Cin, Cout)
+        Hout, Wout = oracle.conv_output_shape(H, W, kh, kw, stride, pad)
+        if dtype == "i8":
+            old = rng.integers(-1000, 1000, size=(batch, Hout, Wout, Cout)).astype(np.int32)
+            alpha, beta = 2, -1
+        else:
+            old = rng.standard_normal((batch, Hout, Wout, Cout)).astype(np.float32)
+            alpha, beta = np.float32(1.5), np.float32(0.5)
+        got = oracle.conv2d_nhwc(dtype, x, w, stride, pad, alpha, beta, old)
+        A = oracle.im2row(dtype, x, kh, kw, stride, pad)
+        M, K = A.shape
+        assert np.array_equal(decode(A), oracle.im2row_f32(decode(x).astype(np.float32), kh, kw, stride, pad).astype(np.float64))
+        via_gemm = gemm("row", M, Cout, K, alpha, A, K, w.reshape(K, Cout), Cout, beta, old.reshape(M, Cout), Cout)
+        t = torch.nn.functional.conv2d(torch.from_numpy(decode(x)).permute(0, 3, 1, 2), torch.from_numpy(decode(w)).permute(3, 2, 0, 1),
+                                       stride=stride, padding=pad)
+        want = float(alpha) * t.permute(0, 2, 3, 1).numpy() + float(beta) * old.astype(np.float64)
+        if dtype == "i8":
+            assert np.array_equal(got.reshape(M, Cout), via_gemm)
+            assert np.array_equal(got, want.astype(np.int64))
+        else:
+            assert np.allclose(got.reshape(M, Cout), via_gemm, rtol=0, atol=1e-11)
+            assert np.allclose(got, want, rtol=0, atol=1e-11)
+
+
 # ------------------------------------------------------------ narrowing to 16-bit storage
 def test_narrowing_to_binary16_against_numpy_and_by_hand():
     # every pattern survives the round trip (NaNs stay NaN)
