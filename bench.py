@@ -19,7 +19,8 @@ gpurun_out/bench_detail.json), which carries
     tables with the per-model time summed over the layers that share a shape
     (fp32 as in the paper; the same shapes in fp16 and int8 under "<model>_f16" / "_i8"),
   * "conv_im2row": the convolution layers behind the headline shapes and the VGG16 table, with the im2row
-    matrix read from the image in place, next to the GEMM on a matrix that already exists,
+    matrix read from the image in place, next to the GEMM on a matrix that already exists
+    ("conv_im2row_16_8bit": the headline layers with binary16 and int8 inputs),
   * "solo_mode": the micro-kernel of each data type's large tile run alone on
     LDS-resident random operands - the ceiling this machine sustains,
   * "cpu_baseline": the CPU oracle timed on a bounded slice of the 4096^3 case.
@@ -455,6 +456,39 @@ def main():
                 del c
             torch.cuda.empty_cache()
         detail["conv_im2row"] = convs
+
+        # the same headline layers with binary16 and int8 inputs through conv2d_im2row_ex (in place where Cin is a
+        # multiple of the K step, else through the matrix), next to the GEMM of the same type on an existing matrix
+        class ConvCaseTyped:
+            def __init__(self, dtype, geom, seed):
+                H, W, Cin, Cout, kh, kw, stride, pad = geom
+                self.dtype = dtype
+                self.geom = (1, H, W, Cin, Cout, kh, kw, stride, stride, pad, pad)
+                Hout, Wout, self.M, self.N, self.K = mg.conv2d_im2row_shape(*self.geom)
+                gen = wl.normal_f16_bits if dtype == "f16" else wl.uniform_i8
+                self.image, self.filt = dev(gen(seed, "row", H * W, Cin)), dev(gen(seed + 1, "row", kh * kw * Cin, Cout))
+                self.out = torch.zeros(self.M * self.N, dtype=torch.int32 if dtype == "i8" else torch.float32, device="cuda")
+                self.ws = torch.empty(max(16, mg.conv2d_im2row_ex_workspace_bytes(code[dtype], *self.geom)), dtype=torch.uint8, device="cuda")
+
+            def run(self, on=stream):
+                mg.conv2d_im2row_ex(code[self.dtype], *self.geom, 1, self.image, self.filt, 0, self.out, self.ws, on)
+
+        typed = []
+        for dtype in ("f16", "i8"):
+            gemm_us_t = {(r["M"], r["N"], r["K"]): r["us"] for r in models["resnet50_v1.5_" + dtype]["layers"]}
+            for i, geom in enumerate(wl.RESNET50_HEADLINE_CONVS):
+                c = ConvCaseTyped(dtype, geom, 8500 + i)
+                for _ in range(3):
+                    c.run()
+                us = (timed([c], 1) if args.once else timed_graph(c, 50)) * 1e3
+                typed.append({"dtype": dtype, "H": geom[0], "W": geom[1], "Cin": geom[2], "Cout": geom[3], "kh": geom[4], "kw": geom[5],
+                              "stride": geom[6], "pad": geom[7], "M": c.M, "N": c.N, "K": c.K,
+                              "path": {1: "in place", 2: "im2row matrix"}[mg.conv2d_im2row_last_path()],
+                              "kernel": mg.gemm_kernel_name(code[dtype], mg.gemm_last_kernel_id()), "split": mg.gemm_last_split(),
+                              "us": round(us, 2), "gemm_us": gemm_us_t.get((c.M, c.N, c.K))})
+                del c
+            torch.cuda.empty_cache()
+        detail["conv_im2row_16_8bit"] = typed
 
         # ---------------- solo mode: the micro-kernel of each data type's large-problem tile alone
         # (operands resident in LDS, pseudo-random values), the measured ceiling of that kernel here

@@ -12,8 +12,9 @@
  * chain of MFMA instructions on accumulators held in registers.
  *
  * Common conventions for the GEMM entry points (gemm_f32, gemm_f16, gemm_bf16,
- * gemm_i8, gemm_f16_c16, gemm_bf16_c16; gemm_ex adds transposed operands, the
- * convolution calls further down state their own arguments)
+ * gemm_i8, gemm_f16_c16, gemm_bf16_c16; gemm_ex adds transposed operands,
+ * gemm_ex_static_ws needs no workspace, the convolution calls further down
+ * state their own arguments)
  * --------------------------------------------------------------------------
  * layout   MI_GEMM_COL_MAJOR: X(i,j) is X[i + j*ldx];  MI_GEMM_ROW_MAJOR:
  *          X(i,j) is X[i*ldx + j].  One layout applies to A, B and C.  Only
@@ -183,6 +184,27 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
 size_t conv2d_im2row_workspace_bytes(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh,
                                      int64_t kw, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w);
 const char *conv2d_im2row_status_string(int status);
+
+/* The same convolution for any data type, as gemm_ex is to gemm_f32 (the data-type retargeting of the paper's
+ * Sec. "Data types" applied to the im2row GEMMs of its Sec. "Rectangular Matrices"): image and filter hold fp32,
+ * binary16 or bfloat16 bit patterns, or int8; the sum is accumulated in fp32 (int32 for int8) and the output is
+ * fp32 (int32), in and out; alpha and beta are host pointers to a float (an int32 for int8).  Same layouts,
+ * zero padding, stream, ownership and workspace rules as conv2d_im2row_f32.  For the 16- and 8-bit types the
+ * kernels read the im2row matrix from the image in place when Cin is a multiple of their K step (32 elements
+ * of 16 bits, 64 of 8 bits), the image is smaller than 2 GiB and Cout is at least 2 (4 for int8); otherwise the
+ * matrix is written into the workspace (M*K elements of the input type) and the GEMM runs on it.
+ * conv2d_im2row_ex_workspace_bytes gives a workspace that suffices for either.  Status -k names the k-th
+ * argument of this list (conv2d_im2row_ex_status_string); -19 = the geometry needs the im2row matrix and the
+ * workspace is too small for it. */
+int conv2d_im2row_ex(int dtype, int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                     int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                     const void *alpha, const void *image, const void *filter,
+                     const void *beta, void *output,
+                     void *workspace, size_t workspace_bytes, void *stream);
+size_t conv2d_im2row_ex_workspace_bytes(int dtype, int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                        int64_t kh, int64_t kw, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                        int64_t pad_w);
+const char *conv2d_im2row_ex_status_string(int status);
 
 /* Output extent and GEMM sizes of that convolution (pure host computation); any output pointer may be
  * NULL.  Returns 0 or the -k of conv2d_im2row_f32's geometry arguments. */

@@ -69,6 +69,12 @@ def load():
     lib.gemm_solo.argtypes = [ci, ci, ci, ci, ci, vp]
     lib.conv2d_im2row_f32.restype = ci
     lib.conv2d_im2row_f32.argtypes = [i64] * 11 + [ctypes.c_float, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+    lib.conv2d_im2row_ex.restype = ci
+    lib.conv2d_im2row_ex.argtypes = [ci] + [i64] * 11 + [vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.conv2d_im2row_ex_workspace_bytes.restype = sz
+    lib.conv2d_im2row_ex_workspace_bytes.argtypes = [ci] + [i64] * 11
+    lib.conv2d_im2row_ex_status_string.restype = ctypes.c_char_p
+    lib.conv2d_im2row_ex_status_string.argtypes = [ci]
     lib.conv2d_im2row_workspace_bytes.restype = sz
     lib.conv2d_im2row_workspace_bytes.argtypes = [i64] * 11
     lib.conv2d_im2row_status_string.restype = ctypes.c_char_p
@@ -242,6 +248,24 @@ def conv2d_im2row_f32(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h,
     if check and status != 0:
         raise GemmError(status, conv2d_im2row_status_string(status))
     return status
+
+
+def conv2d_im2row_ex(dtype, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, alpha, image, filter, beta, output,
+                     workspace=None, stream=None, check=True):
+    """The convolution for any data type; alpha and beta are Python numbers."""
+    lib = load()
+    ws, ws_bytes = _ws(workspace)
+    scal = ctypes.c_int32 if dtype == I8 else ctypes.c_float
+    a, b = scal(alpha), scal(beta)
+    status = lib.conv2d_im2row_ex(dtype, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, ctypes.byref(a),
+                                  _addr(image), _addr(filter), ctypes.byref(b), _addr(output), ws, ws_bytes, _stream(stream))
+    if check and status != 0:
+        raise GemmError(status, lib.conv2d_im2row_ex_status_string(status).decode())
+    return status
+
+
+def conv2d_im2row_ex_workspace_bytes(dtype, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w):
+    return int(load().conv2d_im2row_ex_workspace_bytes(dtype, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w))
 
 
 def conv2d_im2row_workspace_bytes(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w):

@@ -401,9 +401,9 @@ int conv_geometry(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout
 
 // The fused kernels read the image through 32-bit lane offsets; the element-by-element variant splits
 // k into (filter row, element of the run) in single precision, exact below 2^22.
-bool conv_fused_ok(int64_t batch, const ConvGeometry &c)
+bool conv_fused_ok(int64_t batch, const ConvGeometry &c, int es = 4)
 {
-    const unsigned __int128 image_bytes = (unsigned __int128)batch * c.g.H * c.g.W * (unsigned __int128)c.g.Cin * 4u;
+    const unsigned __int128 image_bytes = (unsigned __int128)batch * c.g.H * c.g.W * (unsigned __int128)c.g.Cin * (unsigned)es;
     // the kernels also form offsets of padded positions ((W - iw)*Cin, -iw*Cin, rows above and below the
     // image) in 32-bit integers: the padded image of one batch entry must fit them as well
     const unsigned __int128 padded_row = (unsigned __int128)(c.g.W + 2 * (int64_t)c.g.pad_w) * (unsigned __int128)c.g.Cin;
@@ -425,20 +425,20 @@ LaunchFn conv_fused_launcher(const KernelInfo *ki, const ConvGeometry &c, bool i
 
 // Best fused configuration (canonical problem N x M x K) for a workspace that holds `fit` partial tiles;
 // -1 if none.
-int conv_fused_kernel(const ConvGeometry &c, int64_t fit, bool image_aligned, double *us)
+int conv_fused_kernel(int dtype, const ConvGeometry &c, int64_t fit, bool image_aligned, double *us)
 {
     int best = -1;
     double best_us = 0.0;
-    const Forced f = t_forced[MI_GEMM_F32];
-    for (int id = 0; id < kernel_count(MI_GEMM_F32); ++id) {
-        const KernelInfo *ki = kernel_info(MI_GEMM_F32, id);
+    const Forced f = t_forced[dtype];
+    for (int id = 0; id < kernel_count(dtype); ++id) {
+        const KernelInfo *ki = kernel_info(dtype, id);
         if (!conv_fused_launcher(ki, c, image_aligned) || !can_address(ki, c.N, 0)) continue;
         if (f.id >= 0 ? id != f.id : ki->prio <= 0) continue;
-        int s = auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit);
+        int s = auto_split(dtype, ki, c.N, c.M, c.K, fit);
         // a direct-to-LDS kernel that would need its K split (few tiles, every step latency-bound) loses to
         // the register-direct kernels in every layer measured: it competes unsplit only
         if (ki->waves_k == 0 && f.split < 1) s = 1;
-        double t = predict_us(MI_GEMM_F32, ki, c.N, c.M, c.K, s);
+        double t = predict_us(dtype, ki, c.N, c.M, c.K, s);
         // measured against the GEMM on a matrix that exists: the direct-to-LDS kernels pay for the clamped
         // addresses and the zeroing between the wait and the barrier of every K step, the register-direct
         // ones for the masks of their loads
@@ -450,6 +450,103 @@ int conv_fused_kernel(const ConvGeometry &c, int64_t fit, bool image_aligned, do
 }
 
 size_t round16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+// The convolution entry points.  Status codes are those of conv2d_im2row_f32's argument list.
+int conv_run(int dtype, int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw, int64_t stride_h,
+             int64_t stride_w, int64_t pad_h, int64_t pad_w, uint32_t alpha_bits, bool alpha_zero, const void *image,
+             const void *filter, uint32_t beta_bits, bool beta_zero, bool beta_one, void *output, void *workspace,
+             size_t workspace_bytes, void *stream)
+{
+    static const int kEs[NUM_DTYPES] = {4, 2, 1, 2};
+    const int es = kEs[dtype];
+    t_conv_path = 0;
+    t_last_id = -1;
+    t_last_split = 0;
+    ConvGeometry c;
+    const int bad = conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c);
+    if (bad) return bad;
+    if (workspace != nullptr && (uintptr_t)workspace % 16 != 0) return -17;
+    if (output == nullptr) return -16;
+    if (alpha_zero) {
+        // output <- beta * output: the GEMM's quick path (K = 0 reads neither operand)
+        return run(dtype, es, MI_GEMM_ROW_MAJOR, c.M, c.N, 0, 0, true, nullptr, 1, nullptr, c.N, beta_bits, beta_zero, beta_one,
+                   output, c.N, nullptr, 0, stream);
+    }
+    if (image == nullptr) return -13;
+    if (filter == nullptr) return -14;
+    const size_t ws_bytes = workspace ? workspace_bytes : 0;
+    const size_t matrix_bytes = round16((size_t)c.M * (size_t)c.K * (size_t)es);
+
+    // fused: the im2row matrix is never formed
+    const unsigned __int128 per = (unsigned __int128)c.M * (unsigned __int128)c.N * 4u;
+    int64_t fit = ws_bytes > 0 ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
+    if (fit > MAX_SPLIT) fit = MAX_SPLIT;
+    if (fit < 1) fit = 1;
+    double fused_us = 0.0;
+    const bool image_aligned = (uintptr_t)image % 16 == 0;
+    // the 16- and 8-bit kernels read the filter in words of 4 bytes along Cout: fewer channels go through the matrix
+    const bool fusable = conv_fused_ok(batch, c, es) && (es == 4 || c.N >= 4 / es);
+    const int fused_id = fusable ? conv_fused_kernel(dtype, c, fit, image_aligned, &fused_us) : -1;
+    // explicit: the matrix in the workspace, then the GEMM with what is left of it
+    const bool explicit_fits = ws_bytes >= matrix_bytes;
+    bool fused = fused_id >= 0;
+    if (t_conv_forced_path == 2 || !fused) {
+        if (!explicit_fits) return -18;
+        fused = false;
+    } else if (t_conv_forced_path == 0 && explicit_fits && t_forced[dtype].id < 0) {
+        const int gid = auto_kernel(dtype, c.N, c.M, c.K, c.N, c.K, 1, true, false, false);
+        const double explicit_us = predict_us(dtype, kernel_info(dtype, gid), c.N, c.M, c.K, 1) + kIm2rowFixedUs +
+                                   (double)matrix_bytes / kIm2rowBytesPerUs;
+        if (explicit_us < fused_us) fused = false;
+    }
+
+    hipStream_t st = (hipStream_t)stream;
+    if (!fused) {
+        hipError_t e = launch_im2row_matrix(es, image, workspace, c.M, c.K, c.g, st);
+        if (e != hipSuccess) return (int)e;
+        const int rc = run(dtype, es, MI_GEMM_ROW_MAJOR, c.M, c.N, c.K, alpha_bits, false, workspace, c.K, filter, c.N, beta_bits,
+                           beta_zero, beta_one, output, c.N, ws_bytes > matrix_bytes ? (char *)workspace + matrix_bytes : nullptr,
+                           ws_bytes - matrix_bytes, stream);
+        if (rc == 0) t_conv_path = 2;
+        return rc < 0 ? -17 : rc;      // the GEMM's own argument checks cannot fail here except through the workspace
+    }
+
+    const KernelInfo *ki = kernel_info(dtype, fused_id);
+    const Forced f = t_forced[dtype];
+    const int64_t ktiles = ceil_div(c.K, ki->BK);
+    int64_t sp = f.split >= 1 ? f.split : (ki->waves_k == 0 ? 1 : auto_split(dtype, ki, c.N, c.M, c.K, fit));
+    if (sp > ktiles) sp = ktiles;
+    if (sp > fit) sp = fit;
+    if (sp < 1) sp = 1;
+    Params p;
+    memset(&p, 0, sizeof(p));
+    p.A = filter; p.B = image; p.C = output; p.ws = workspace;
+    p.lda = c.N; p.ldb = 0; p.ldc = c.N;
+    p.M = (int)c.N; p.N = (int)c.M; p.K = (int)c.K;
+    p.tiles_m = (int)ceil_div(c.N, ki->BM);
+    p.tiles_n = (int)ceil_div(c.M, ki->BN);
+    if ((int64_t)p.tiles_m * p.tiles_n > INT_MAX) return -1;
+    p.ktiles = (int)ktiles;
+    p.ktiles_per_split = (int)ceil_div(ktiles, sp);
+    p.split = (int)ceil_div(ktiles, p.ktiles_per_split);
+    p.alpha_bits = alpha_bits;
+    p.beta_bits = beta_bits;
+    p.use_beta = beta_zero ? 0 : 1;
+    p.group_m = 8;
+    p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
+    p.conv = c.g;
+    p.vecA = aligned16(filter, c.N, es) ? 1 : 0;
+    hipError_t e = conv_fused_launcher(ki, c, image_aligned)(p, st);
+    if (e != hipSuccess) return (int)e;
+    if (p.split > 1) {
+        e = launch_reduce(dtype, workspace, output, p.M, p.N, p.ldc, p.split, p.alpha_bits, p.beta_bits, p.use_beta, st);
+        if (e != hipSuccess) return (int)e;
+    }
+    t_last_id = fused_id;
+    t_last_split = p.split;
+    t_conv_path = 1;
+    return 0;
+}
 
 }  // namespace
 
@@ -678,90 +775,29 @@ int conv2d_im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t 
                       const float *filter, float beta, float *output, void *workspace, size_t workspace_bytes,
                       void *stream)
 {
-    t_conv_path = 0;
-    t_last_id = -1;
-    t_last_split = 0;
-    ConvGeometry c;
-    const int bad = conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c);
-    if (bad) return bad;
-    if (workspace != nullptr && (uintptr_t)workspace % 16 != 0) return -17;
-    if (output == nullptr) return -16;
-    if (alpha == 0.0f) {
-        // output <- beta * output: the GEMM entry point's quick path (K = 0 reads neither operand)
-        return gemm_f32(MI_GEMM_ROW_MAJOR, c.M, c.N, 0, 0.0f, nullptr, 1, nullptr, c.N, beta, output, c.N, nullptr, 0, stream);
-    }
-    if (image == nullptr) return -13;
-    if (filter == nullptr) return -14;
-    const size_t ws_bytes = workspace ? workspace_bytes : 0;
-    const size_t matrix_bytes = round16((size_t)c.M * (size_t)c.K * 4u);
+    return conv_run(MI_GEMM_F32, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, bits_of(alpha), alpha == 0.0f,
+                    image, filter, bits_of(beta), beta == 0.0f, beta == 1.0f, output, workspace, workspace_bytes, stream);
+}
 
-    // fused: the im2row matrix is never formed
-    const unsigned __int128 per = (unsigned __int128)c.M * (unsigned __int128)c.N * 4u;
-    int64_t fit = ws_bytes > 0 ? (int64_t)((unsigned __int128)ws_bytes / per) : 0;
-    if (fit > MAX_SPLIT) fit = MAX_SPLIT;
-    if (fit < 1) fit = 1;
-    double fused_us = 0.0;
-    const bool image_aligned = (uintptr_t)image % 16 == 0;
-    const int fused_id = conv_fused_ok(batch, c) ? conv_fused_kernel(c, fit, image_aligned, &fused_us) : -1;
-    // explicit: the matrix in the workspace, then the GEMM with what is left of it
-    const bool explicit_fits = ws_bytes >= matrix_bytes;
-    bool fused = fused_id >= 0;
-    if (t_conv_forced_path == 2 || !fused) {
-        if (!explicit_fits) return -18;
-        fused = false;
-    } else if (t_conv_forced_path == 0 && explicit_fits && t_forced[MI_GEMM_F32].id < 0) {
-        const int gid = auto_kernel(MI_GEMM_F32, c.N, c.M, c.K, c.N, c.K, 1, true, false, false);
-        const double explicit_us = predict_us(MI_GEMM_F32, kernel_info(MI_GEMM_F32, gid), c.N, c.M, c.K, 1) + kIm2rowFixedUs +
-                                   (double)matrix_bytes / kIm2rowBytesPerUs;
-        if (explicit_us < fused_us) fused = false;
+int conv2d_im2row_ex(int dtype, int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh, int64_t kw,
+                     int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, const void *alpha, const void *image,
+                     const void *filter, const void *beta, void *output, void *workspace, size_t workspace_bytes,
+                     void *stream)
+{
+    if (dtype < 0 || dtype >= NUM_DTYPES) return -1;
+    if (alpha == nullptr) return -13;
+    if (beta == nullptr) return -16;
+    int rc;
+    if (dtype == MI_GEMM_I8) {
+        const int32_t a = *(const int32_t *)alpha, b = *(const int32_t *)beta;
+        rc = conv_run(dtype, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, (uint32_t)a, a == 0, image, filter,
+                      (uint32_t)b, b == 0, b == 1, output, workspace, workspace_bytes, stream);
+    } else {
+        const float a = *(const float *)alpha, b = *(const float *)beta;
+        rc = conv_run(dtype, batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, bits_of(a), a == 0.0f, image, filter,
+                      bits_of(b), b == 0.0f, b == 1.0f, output, workspace, workspace_bytes, stream);
     }
-
-    hipStream_t st = (hipStream_t)stream;
-    if (!fused) {
-        hipError_t e = launch_im2row_matrix(image, (float *)workspace, c.M, c.K, c.g, st);
-        if (e != hipSuccess) return (int)e;
-        const int rc = gemm_f32(MI_GEMM_ROW_MAJOR, c.M, c.N, c.K, alpha, (const float *)workspace, c.K, filter, c.N, beta,
-                                output, c.N, ws_bytes > matrix_bytes ? (char *)workspace + matrix_bytes : nullptr,
-                                ws_bytes - matrix_bytes, stream);
-        if (rc == 0) t_conv_path = 2;
-        return rc < 0 ? -17 : rc;      // the GEMM's own argument checks cannot fail here except through the workspace
-    }
-
-    const KernelInfo *ki = kernel_info(MI_GEMM_F32, fused_id);
-    const Forced f = t_forced[MI_GEMM_F32];
-    const int64_t ktiles = ceil_div(c.K, ki->BK);
-    int64_t sp = f.split >= 1 ? f.split : (ki->waves_k == 0 ? 1 : auto_split(MI_GEMM_F32, ki, c.N, c.M, c.K, fit));
-    if (sp > ktiles) sp = ktiles;
-    if (sp > fit) sp = fit;
-    if (sp < 1) sp = 1;
-    Params p;
-    memset(&p, 0, sizeof(p));
-    p.A = filter; p.B = image; p.C = output; p.ws = workspace;
-    p.lda = c.N; p.ldb = 0; p.ldc = c.N;
-    p.M = (int)c.N; p.N = (int)c.M; p.K = (int)c.K;
-    p.tiles_m = (int)ceil_div(c.N, ki->BM);
-    p.tiles_n = (int)ceil_div(c.M, ki->BN);
-    if ((int64_t)p.tiles_m * p.tiles_n > INT_MAX) return -1;
-    p.ktiles = (int)ktiles;
-    p.ktiles_per_split = (int)ceil_div(ktiles, sp);
-    p.split = (int)ceil_div(ktiles, p.ktiles_per_split);
-    p.alpha_bits = bits_of(alpha);
-    p.beta_bits = bits_of(beta);
-    p.use_beta = beta == 0.0f ? 0 : 1;
-    p.group_m = 8;
-    p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
-    p.conv = c.g;
-    p.vecA = aligned16(filter, c.N, 4) ? 1 : 0;
-    hipError_t e = conv_fused_launcher(ki, c, image_aligned)(p, st);
-    if (e != hipSuccess) return (int)e;
-    if (p.split > 1) {
-        e = launch_reduce(MI_GEMM_F32, workspace, output, p.M, p.N, p.ldc, p.split, p.alpha_bits, p.beta_bits, p.use_beta, st);
-        if (e != hipSuccess) return (int)e;
-    }
-    t_last_id = fused_id;
-    t_last_split = p.split;
-    t_conv_path = 1;
-    return 0;
+    return rc < 0 ? rc - 1 : rc;        // conv_run numbers the arguments of conv2d_im2row_f32; here dtype comes first
 }
 
 int im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t kh, int64_t kw, int64_t stride_h, int64_t stride_w,
@@ -772,7 +808,7 @@ int im2row_f32(int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t kh, int
     if (bad) return bad <= -5 ? bad + 1 : bad;       // this list has no Cout
     if (image == nullptr) return -11;
     if (matrix == nullptr) return -12;
-    hipError_t e = launch_im2row_matrix(image, matrix, c.M, c.K, c.g, (hipStream_t)stream);
+    hipError_t e = launch_im2row_matrix(4, image, matrix, c.M, c.K, c.g, (hipStream_t)stream);
     return e == hipSuccess ? 0 : (int)e;
 }
 
@@ -798,6 +834,32 @@ size_t conv2d_im2row_workspace_bytes(int64_t batch, int64_t H, int64_t W, int64_
     if (conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c)) return 0;
     // room for the im2row matrix and for the GEMM's (or the fused kernel's) partial tiles
     return round16((size_t)c.M * (size_t)c.K * 4u) + round16(gemm_workspace_bytes(MI_GEMM_F32, c.M, c.N, c.K));
+}
+
+size_t conv2d_im2row_ex_workspace_bytes(int dtype, int64_t batch, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t kh,
+                                        int64_t kw, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w)
+{
+    static const size_t es[NUM_DTYPES] = {4, 2, 1, 2};
+    ConvGeometry c;
+    if (dtype < 0 || dtype >= NUM_DTYPES) return 0;
+    if (conv_geometry(batch, H, W, Cin, Cout, kh, kw, stride_h, stride_w, pad_h, pad_w, true, &c)) return 0;
+    return round16((size_t)c.M * (size_t)c.K * es[dtype]) + round16(gemm_workspace_bytes(dtype, c.M, c.N, c.K));
+}
+
+const char *conv2d_im2row_ex_status_string(int status)
+{
+    if (status == -1) return "argument 1 (dtype) is not MI_GEMM_F32, MI_GEMM_F16, MI_GEMM_I8 or MI_GEMM_BF16";
+    if (status == -13) return "argument 13 (alpha) is NULL";
+    if (status == -16) return "argument 16 (beta) is NULL";
+    if (status < -1 && status >= -19) {
+        // the text of conv2d_im2row_f32's list with the position in this one
+        static thread_local char buf[200];
+        const char *text = conv2d_im2row_status_string(status + 1);
+        const char *paren = strchr(text, '(');
+        snprintf(buf, sizeof(buf), "argument %d %s", -status, paren ? paren : text);
+        return buf;
+    }
+    return conv2d_im2row_status_string(status);
 }
 
 const char *conv2d_im2row_status_string(int status)

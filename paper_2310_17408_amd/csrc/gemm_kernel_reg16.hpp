@@ -18,6 +18,11 @@
 // and fragments that lie wholly inside K are loaded as usual, a fragment that straddles K element by
 // element, the rest is zero.  Loads are issued at element alignment (the memory system splits
 // misaligned ones).
+//
+// IM2ROW: the K-contiguous operand B is the im2row matrix of a channels-last image (paper Sec.
+// "Rectangular Matrices"), read from the image in place: row n is an output pixel, and with Cin a
+// multiple of the K step a step lies inside one filter tap, so a lane's fragment is 16 contiguous
+// bytes of the image, or zeros where the tap falls outside it (the load is then not issued).
 #pragma once
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_reg32.hpp"
@@ -103,7 +108,7 @@ struct Reg16Micro {
 template <bool V>
 struct WithShift { static constexpr bool value = V; };
 
-template <class T>
+template <class T, bool IM2ROW = false>
 __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg16(const Params p)
 {
     typedef typename T::DT DT;
@@ -161,16 +166,41 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg16(const Params
         aoff[t] = a_by_element ? 0u : (uint32_t)(((int64_t)(KCH * g + t) * p.lda + (mword - mbase)) * ES);
     uint32_t boff[TN];
     int nrow[TN];
+    int ih0[IM2ROW ? TN : 1], iw0[IM2ROW ? TN : 1];            // IM2ROW: image position of the pixel's tap (0, 0)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         int n = nw + 16 * j + r;
         nrow[j] = n < p.N ? n : p.N - 1;
-        boff[j] = (uint32_t)(((int64_t)(nrow[j] - nw) * p.ldb + KCH * g) * ES);
+        if constexpr (IM2ROW) {
+            const int per_image = p.conv.Hout * p.conv.Wout;
+            const int b = nrow[j] / per_image, rem = nrow[j] - b * per_image;
+            const int oh = rem / p.conv.Wout, ow = rem - oh * p.conv.Wout;
+            ih0[j] = oh * p.conv.stride_h - p.conv.pad_h;
+            iw0[j] = ow * p.conv.stride_w - p.conv.pad_w;
+            // from the address the tap (0, 0) of a pixel at (0, 0) without padding would have: never negative
+            boff[j] = (uint32_t)((((int64_t)(b * p.conv.H + oh * p.conv.stride_h) * p.conv.W + ow * p.conv.stride_w) *
+                                      p.conv.Cin + KCH * g) * ES);
+        } else {
+            boff[j] = (uint32_t)(((int64_t)(nrow[j] - nw) * p.ldb + KCH * g) * ES);
+        }
     }
     const MIG_GLOBAL unsigned char *a_wave =
         (const MIG_GLOBAL unsigned char *)((const elt *)p.A + (int64_t)k_begin * p.lda + mbase);
-    const MIG_GLOBAL unsigned char *b_wave =
-        (const MIG_GLOBAL unsigned char *)((const elt *)p.B + (int64_t)nw * p.ldb + k_begin);
+    // IM2ROW: the tap (tap_r, tap_s) and the channel tap_c the wave's next step starts at; b_wave points pad_h
+    // rows and pad_w pixels before that tap of pixel (0, 0) (an address that is only ever used with a lane
+    // offset that brings it inside the image)
+    int tap_r = 0, tap_s = 0, tap_c = 0;
+    const MIG_GLOBAL unsigned char *b_wave;
+    if constexpr (IM2ROW) {
+        const int tap = k_begin / p.conv.Cin;
+        tap_c = k_begin - tap * p.conv.Cin;
+        tap_r = tap / p.conv.kw;
+        tap_s = tap - tap_r * p.conv.kw;
+        b_wave = (const MIG_GLOBAL unsigned char *)((const elt *)p.B +
+                 ((int64_t)(tap_r - p.conv.pad_h) * p.conv.W + (tap_s - p.conv.pad_w)) * p.conv.Cin + tap_c);
+    } else {
+        b_wave = (const MIG_GLOBAL unsigned char *)((const elt *)p.B + (int64_t)nw * p.ldb + k_begin);
+    }
     const int64_t a_step = (int64_t)BK * p.lda * ES;
 
     // ---- element-wise loads of the step that starts `kofs` elements into the wave's K range, of
@@ -272,10 +302,29 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg16(const Params
         for (int j = 0; j < TN; ++j) {
             uint32_t o = boff[j];
             asm volatile("" : "+v"(o));
-            x.b[j] = *(const MIG_GLOBAL v4i_u *)(sb + o);
+            if constexpr (IM2ROW) {
+                const bool inside = (uint32_t)(ih0[j] + tap_r) < (uint32_t)p.conv.H && (uint32_t)(iw0[j] + tap_s) < (uint32_t)p.conv.W;
+                v4i v = {0, 0, 0, 0};
+                if (inside) v = *(const MIG_GLOBAL v4i_u *)(sb + o);
+                x.b[j] = v;
+            } else {
+                x.b[j] = *(const MIG_GLOBAL v4i_u *)(sb + o);
+            }
         }
         pa += a_step;
         pb += BK * ES;
+        if constexpr (IM2ROW) {
+            // the taps of one filter row are contiguous in the image; the next filter row is one image row on
+            tap_c += BK;
+            if (tap_c == p.conv.Cin) {
+                tap_c = 0;
+                if (++tap_s == p.conv.kw) {
+                    tap_s = 0;
+                    ++tap_r;
+                    pb += (int64_t)(p.conv.W - p.conv.kw) * p.conv.Cin * ES;
+                }
+            }
+        }
     };
 
     accv acc[TM][TN];

@@ -261,7 +261,14 @@ template <class T>
 static hipError_t launch_tile_reg16(const Params &p, hipStream_t stream)
 {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
-    hipLaunchKernelGGL(gemm_kernel_reg16<T>, grid, dim3(T::NT), 0, stream, p);   // its LDS is static
+    hipLaunchKernelGGL((gemm_kernel_reg16<T, false>), grid, dim3(T::NT), 0, stream, p);   // its LDS is static
+    return hipGetLastError();
+}
+template <class T>
+static hipError_t launch_tile_reg16_im2row(const Params &p, hipStream_t stream)
+{
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL((gemm_kernel_reg16<T, true>), grid, dim3(T::NT), 0, stream, p);
     return hipGetLastError();
 }
 template <class T>
@@ -276,7 +283,7 @@ static constexpr KernelInfo info_reg16(const char *name, int prio, int eff_pct, 
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg16<T>, prio, eff_pct, step_ns, setup_ns,
                       &solo_reg16<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
-                      fill_bytes_per_us, 30};
+                      fill_bytes_per_us, 30, 0, &launch_tile_reg16_im2row<T>, nullptr};
 }
 
 template <class T>

@@ -80,8 +80,9 @@ const KernelInfo *kernel_info(int dtype, int id);  // nullptr if out of range
 
 hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
                          uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream, int c_type = C_WIDE);
-// The im2row matrix [rows][K] (row-major, K = kh*kw*Cin, kh given by K) of a channels-last fp32 image.
-hipError_t launch_im2row_matrix(const float *image, float *matrix, int64_t rows, int64_t K, const Im2row &g,
+// The im2row matrix [rows][K] (row-major, K = kh*kw*Cin, kh given by K) of a channels-last image whose
+// elements have `es` bytes (4, 2 or 1), in the same type.
+hipError_t launch_im2row_matrix(int es, const void *image, void *matrix, int64_t rows, int64_t K, const Im2row &g,
                                 hipStream_t stream);
 hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
                         hipStream_t stream, int c_type = C_WIDE);

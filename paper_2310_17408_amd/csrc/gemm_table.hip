@@ -26,7 +26,8 @@ static const KernelInfo *table_of(int dtype, int *count)
 // The im2row transform written out (paper Sec. "Rectangular Matrices"): element (row, k) of the
 // matrix, row = (b, oh, ow), k = (r, s, c), is the image element the tap (r, s) of that output pixel
 // meets, or zero outside the image.  Used for geometries the fused kernels do not take.
-__global__ void __launch_bounds__(256) im2row_matrix_kernel(const float *__restrict__ image, float *__restrict__ matrix,
+template <class E>
+__global__ void __launch_bounds__(256) im2row_matrix_kernel(const E *__restrict__ image, E *__restrict__ matrix,
                                                             int64_t rows, int64_t K, const Im2row g)
 {
     const int64_t total = rows * K;
@@ -40,7 +41,7 @@ __global__ void __launch_bounds__(256) im2row_matrix_kernel(const float *__restr
         const int b = (int)(row / per_image), rem = (int)(row - (int64_t)b * per_image);
         const int oh = rem / g.Wout, ow = rem - oh * g.Wout;
         const int ih = oh * g.stride_h - g.pad_h + r, iw = ow * g.stride_w - g.pad_w + s;
-        float v = 0.0f;
+        E v = 0;                                              // all-zero bits are the value 0 in every type
         if ((uint32_t)ih < (uint32_t)g.H && (uint32_t)iw < (uint32_t)g.W)
             v = image[(((int64_t)b * g.H + ih) * g.W + iw) * g.Cin + c];
         matrix[idx] = v;
@@ -82,10 +83,16 @@ hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64
     return hipGetLastError();
 }
 
-hipError_t launch_im2row_matrix(const float *image, float *matrix, int64_t rows, int64_t K, const Im2row &g,
+hipError_t launch_im2row_matrix(int es, const void *image, void *matrix, int64_t rows, int64_t K, const Im2row &g,
                                 hipStream_t stream)
 {
-    hipLaunchKernelGGL(im2row_matrix_kernel, dim3(blocks_for(rows * K)), dim3(256), 0, stream, image, matrix, rows, K, g);
+    const dim3 grid(blocks_for(rows * K));
+    if (es == 4)
+        hipLaunchKernelGGL(im2row_matrix_kernel<uint32_t>, grid, dim3(256), 0, stream, (const uint32_t *)image, (uint32_t *)matrix, rows, K, g);
+    else if (es == 2)
+        hipLaunchKernelGGL(im2row_matrix_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t *)image, (uint16_t *)matrix, rows, K, g);
+    else
+        hipLaunchKernelGGL(im2row_matrix_kernel<uint8_t>, grid, dim3(256), 0, stream, (const uint8_t *)image, (uint8_t *)matrix, rows, K, g);
     return hipGetLastError();
 }
 

@@ -47,7 +47,7 @@ namespace mig {
 int kernel_count(int dtype) { return (dtype >= 0 && dtype < 4) ? (int)(sizeof(g_table) / sizeof(g_table[0])) : 0; }
 const KernelInfo *kernel_info(int dtype, int id) { return (id >= 0 && id < kernel_count(dtype)) ? &g_table[id] : nullptr; }
 hipError_t launch_reduce(int, const void *, void *, int, int, int64_t, int, uint32_t, uint32_t, int, hipStream_t, int) { ++g_reduces; return hipSuccess; }
-hipError_t launch_im2row_matrix(const float *, float *, int64_t, int64_t, const Im2row &, hipStream_t) { ++g_matrices; return hipSuccess; }
+hipError_t launch_im2row_matrix(int, const void *, void *, int64_t, int64_t, const Im2row &, hipStream_t) { ++g_matrices; return hipSuccess; }
 hipError_t launch_scale(int, void *, int, int, int64_t, uint32_t, int, hipStream_t, int) { ++g_scales; return hipSuccess; }
 }
 extern "C" const char *hipGetErrorString(hipError_t) { return "hip error (stand-in)"; }
@@ -135,6 +135,22 @@ int main()
     EXPECT(conv2d_im2row_f32(1, 4, 4, 1 << 19, 8, 3, 3, 1, 1, 1 << 11, 1 << 11, 1.f, P, P, 0.f, P, nullptr, 0, nullptr) == -18);
     EXPECT(conv2d_im2row_force_path(3) == -1 && conv2d_im2row_force_path(0) == 0);
     EXPECT(im2row_f32(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, P, P, nullptr) == 0 && g_matrices == 1);
+    // the convolution for the other data types: its own argument positions; in place when Cin is a multiple of the
+    // K step of a configuration (the stand-ins' 16 and 32), through the matrix otherwise
+    const int32_t ione = 1, izero = 0;
+    g_launches = g_matrices = 0;
+    EXPECT(conv2d_im2row_ex(7, 1, 14, 14, 32, 40, 3, 3, 2, 2, 1, 1, &one, P, P, &zero, P, nullptr, 0, nullptr) == -1);
+    EXPECT(conv2d_im2row_ex(MI_GEMM_F16, 1, 14, 14, 32, 40, 3, 3, 2, 2, 1, 1, nullptr, P, P, &zero, P, nullptr, 0, nullptr) == -13);
+    EXPECT(conv2d_im2row_ex(MI_GEMM_F16, 1, 14, 14, 32, 40, 0, 3, 2, 2, 1, 1, &one, P, P, &zero, P, nullptr, 0, nullptr) == -7);   // kh is the 7th
+    EXPECT(conv2d_im2row_ex(MI_GEMM_F16, 1, 14, 14, 32, 40, 3, 3, 2, 2, 1, 1, &one, nullptr, P, &zero, P, nullptr, 0, nullptr) == -14);
+    EXPECT(conv2d_im2row_ex(MI_GEMM_F16, 1, 14, 14, 32, 40, 3, 3, 2, 2, 1, 1, &one, P, P, &zero, P, nullptr, 0, nullptr) == 0 && g_launches == 1 && g_matrices == 0);
+    EXPECT(conv2d_im2row_ex(MI_GEMM_I8, 1, 14, 14, 32, 40, 3, 3, 2, 2, 1, 1, &ione, P, P, &izero, P, nullptr, 0, nullptr) == 0 && g_launches == 2);
+    EXPECT(conv2d_im2row_ex(MI_GEMM_I8, 1, 14, 14, 32, 3, 3, 3, 2, 2, 1, 1, &ione, P, P, &izero, P, nullptr, 0, nullptr) == -19);   // Cout < 4: needs the matrix
+    const size_t cws = conv2d_im2row_ex_workspace_bytes(MI_GEMM_I8, 1, 14, 14, 32, 3, 3, 3, 2, 2, 1, 1);
+    EXPECT(cws >= 49 * 288 && cws < 49 * 288 * 4);
+    EXPECT(conv2d_im2row_ex(MI_GEMM_I8, 1, 14, 14, 32, 3, 3, 3, 2, 2, 1, 1, &ione, P, P, &izero, P, WS, cws, nullptr) == 0 && g_matrices == 1);
+    EXPECT(conv2d_im2row_ex_workspace_bytes(9, 1, 14, 14, 32, 3, 3, 3, 2, 2, 1, 1) == 0);
+    EXPECT(strlen(conv2d_im2row_ex_status_string(-19)) > 0 && strlen(conv2d_im2row_ex_status_string(-8)) > 0);
     EXPECT(im2row_f32(1, 8, 8, 4, 3, 3, 0, 1, 1, 1, P, P, nullptr) == -7);
     printf("%s (%d launches recorded)\n", g_failed ? "FAILED" : "ok", g_launches);
     return g_failed ? 1 : 0;
