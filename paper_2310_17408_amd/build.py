@@ -13,7 +13,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmi_gemm.so")
 SOURCES = ["gemm_table_f32.hip", "gemm_table_f16.hip", "gemm_table_bf16.hip", "gemm_table_i8.hip", "gemm_table.hip",
            "gemm_static_ws.hip", "gemm_api.cpp"]
-HEADERS = ["gemm_kernel.hpp", "gemm_kernel_dma.hpp", "gemm_kernel_ring.hpp", "gemm_kernel_dma32.hpp", "gemm_kernel_reg32.hpp",
+HEADERS = ["gemm_kernel.hpp", "gemm_kernel_dma.hpp", "gemm_kernel_ring.hpp", "gemm_kernel_dma32.hpp", "gemm_kernel_dma32t.hpp", "gemm_kernel_reg32.hpp",
            "gemm_kernel_reg16.hpp", "gemm_solo.hpp", "gemm_launchers.hpp", "gemm_table.h",
            os.path.join("..", "..", "include", "mi_gemm.h")]
 

@@ -67,9 +67,14 @@ constexpr int NUM_SIMD = 4 * NUM_CU;
 // the register transposes and, with bank conflicts, into LDS), alone or together with a K-contiguous A:
 // measured at 1024^3 ... 4096^3, the smaller the tile the more.  1 for every other kernel, data type and
 // orientation (the 16- and 8-bit types have direct kernels for these orientations).
-double staged_orientation_factor(int dtype, const KernelInfo *ki, bool a_kc, bool b_nc)
+double staged_orientation_factor(int dtype, const KernelInfo *ki, bool a_kc, bool b_nc, bool aligned = true)
 {
-    if (dtype != MI_GEMM_F32 || !b_nc || !ki->transposed_ok) return 1.0;
+    if (dtype != MI_GEMM_F32 || !(a_kc || b_nc)) return 1.0;
+    // the direct fp32 kernels take transposed operands at their normal speed when rows are 16-byte aligned;
+    // otherwise every tile of theirs goes through guarded loads and registers (measured 2.2 ... 3.2 times
+    // slower at 2050^3 and 1026^3, against which the staged kernels' factors below compete)
+    if (!ki->transposed_ok) return aligned ? 1.0 : 2.6;
+    if (!b_nc) return 1.0;
     const int area = ki->BM * ki->BN;
     if (area <= 64 * 64) return a_kc ? 1.85 : 2.6;
     if (area <= 128 * 128) return a_kc ? 1.45 : 1.9;
@@ -173,7 +178,7 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
                                            : ki->transposed_ok != 0;
         if (!takes) continue;
         if (!can_address(ki, lda, ldb)) continue;
-        const double f = staged_orientation_factor(dtype, ki, a_kc, b_nc);
+        const double f = staged_orientation_factor(dtype, ki, a_kc, b_nc, aligned);
         const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned, f);
         const double t = predict_us(dtype, ki, M, N, K, s, aligned, f);
         if (best < 0 || t < best_us) { best = id; best_us = t; }
@@ -191,7 +196,7 @@ Choice choose_uncached(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, 
     c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
-    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned, staged_orientation_factor(dtype, ki, a_kc, b_nc));
+    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned, staged_orientation_factor(dtype, ki, a_kc, b_nc, aligned));
     if (s > ktiles) s = ktiles;
     if (s > fit) s = fit;
     if (s < 1) s = 1;
@@ -637,20 +642,15 @@ size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
     if (slot.used && slot.dtype == dtype && slot.M == M && slot.N == N && slot.K == K) return slot.bytes;
     // the largest split the model would give any configuration, in either orientation (a row-major call
     // runs the transposed problem), for aligned and unaligned operands, and for every slowdown the model
-    // applies to transposed operands (gemm_ex on the staged fp32 kernels)
+    // applies to transposed operands (gemm_ex on the fp32 kernels)
     static const bool kOrient[4][2] = {{false, false}, {true, false}, {false, true}, {true, true}};
     int64_t smax = 1;
     for (int id = 0; id < kernel_count(dtype); ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
-        double seen[4];
-        int nseen = 0;
         for (int o = 0; o < 4; ++o) {
-            const double f = staged_orientation_factor(dtype, ki, kOrient[o][0], kOrient[o][1]);
-            bool dup = false;
-            for (int j = 0; j < nseen; ++j) dup = dup || seen[j] == f;
-            if (dup) continue;
-            seen[nseen++] = f;
             for (int aligned = 0; aligned < 2; ++aligned) {
+                const double f = staged_orientation_factor(dtype, ki, kOrient[o][0], kOrient[o][1], aligned != 0);
+                if (o > 0 && f == 1.0) continue;                // as the canonical orientation
                 const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT, aligned != 0, f);
                 const int64_t s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT, aligned != 0, f);
                 if (s1 > smax) smax = s1;

@@ -4,6 +4,7 @@
 #include "gemm_kernel.hpp"
 #include "gemm_kernel_dma.hpp"
 #include "gemm_kernel_dma32.hpp"
+#include "gemm_kernel_dma32t.hpp"
 #include "gemm_kernel_ring.hpp"
 #include "gemm_kernel_reg32.hpp"
 #include "gemm_kernel_reg16.hpp"
@@ -176,9 +177,36 @@ static constexpr KernelInfo info_ring(const char *name, int prio, int eff_pct, i
     return k;
 }
 
-template <class T>
+// the fp32 direct kernel for transposed operands (gemm_ex): A with K contiguous and / or B with N contiguous
+template <class T, bool A_KC, bool B_NC>
+static hipError_t launch_dma32t_variant(const Params &p, hipStream_t stream)
+{
+    static bool attr_done[64] = {false};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_done[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel_dma32t<T, A_KC, B_NC>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[dev] = true;
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.split, 1);
+    hipLaunchKernelGGL((gemm_kernel_dma32t<T, A_KC, B_NC>), grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+template <class T, bool TRANSPOSED_TOO>
 static hipError_t launch_tile_dma32(const Params &p, hipStream_t stream)
 {
+    if (p.a_kc || p.b_nc) {
+        if constexpr (TRANSPOSED_TOO) {
+            if (p.a_kc) return p.b_nc ? launch_dma32t_variant<T, true, true>(p, stream) : launch_dma32t_variant<T, true, false>(p, stream);
+            return launch_dma32t_variant<T, false, true>(p, stream);
+        } else {
+            return hipErrorInvalidValue;                // the selector never asks for it (a_kc_ok == b_nc_ok == 0)
+        }
+    }
     static bool attr_done[64] = {false};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -212,11 +240,15 @@ static hipError_t launch_tile_dma32_im2row(const Params &p, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <class T>
+// TRANSPOSED_TOO: the configuration also takes transposed operands (through gemm_kernel_dma32t)
+template <class T, bool TRANSPOSED_TOO = false>
 static constexpr KernelInfo info_dma32(const char *name, int prio, int eff_pct, int floor_ns, int setup_ns = 0)
 {
-    return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T>, prio, eff_pct, floor_ns, setup_ns,
-                      &solo_dma32<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 0, 0, &launch_tile_dma32_im2row<T>, nullptr};
+    KernelInfo k{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_dma32<T, TRANSPOSED_TOO>, prio, eff_pct, floor_ns, setup_ns,
+                 &solo_dma32<T>, T::MINB, 0, 0, 0, 0, 0, 0, 0.0, 0, 0, &launch_tile_dma32_im2row<T>, nullptr};
+    k.a_kc_ok = TRANSPOSED_TOO ? 1 : 0;
+    k.b_nc_ok = TRANSPOSED_TOO ? 1 : 0;
+    return k;
 }
 
 template <class T>

@@ -159,3 +159,29 @@ def test_n_contiguous_b_on_the_square_direct_kernels(dtype):
     for ta in (0, 1):
         k, _ = _case(dtype, "col", ta, 1, 2048, 2048, 1024, 1, 0, seed=7790 + ta)
         assert mg.gemm_kernel_name(DT[dtype], k).endswith(DIRECT)
+
+
+@pytest.mark.parametrize("ta,tb", [(1, 0), (0, 1), (1, 1)])
+def test_fp32_transposed_operands_on_the_direct_kernels(ta, tb):
+    """The fp32 direct-to-LDS configurations that take transposed operands (each operand is staged as it lies in
+    memory; only the fragment index maps change): aligned multi-tile shapes (transfers only), last tiles moved
+    back (at rows that are and are not 16-byte aligned), matrices smaller than a tile, odd leading dimensions
+    (guarded staging), a partial last K step, a K split; the automatic choice for a large aligned problem must be
+    one of them."""
+    names = [mg.gemm_kernel_name(mg.F32, i) for i in range(mg.gemm_kernel_count(mg.F32))]
+    direct = [i for i, nm in enumerate(names) if nm in ("f32_64x64_w32x32_dma", "f32_128x64_w64x32_dma", "f32_128x128_w64x64_dma")]
+    assert len(direct) == 3
+    for kid in direct:
+        for layout in ("col", "row"):
+            k, _ = _case("f32", layout, ta, tb, 512, 384, 256, 1.5, 0.5, seed=7800 + kid, kernel_id=kid)
+            assert k == kid
+            _case("f32", layout, ta, tb, 400, 336, 448, 1.5, 0.5, seed=7810 + kid, kernel_id=kid)        # moved back, aligned rows
+            _case("f32", layout, ta, tb, 402, 331, 203, 1.5, 0.5, seed=7820 + kid, kernel_id=kid)        # moved back, unaligned
+        _case("f32", "col", ta, tb, 300, 270, 200, 1.5, 0.5, seed=7830 + kid, kernel_id=kid, pad=(3, 5, 1))
+        _case("f32", "col", ta, tb, 40, 50, 100, 1.5, 0.0, seed=7840 + kid, kernel_id=kid)
+        k, s = _case("f32", "row", ta, tb, 256, 256, 2048, 1.5, 0.5, seed=7850 + kid, kernel_id=kid, split=4)
+        assert (k, s) == (kid, 4)
+        _case("f32", "col", ta, tb, 150, 140, 1024, 2, -1, seed=7860 + kid, kernel_id=kid, exact=True)
+    k, _ = _case("f32", "col", ta, tb, 2048, 2048, 512, 1.0, 0.0, seed=7870)
+    assert k in direct
+    _case("f32", "col", ta, tb, 1026, 1026, 514, 1.0, 0.0, seed=7880)          # rows of 1026 or 514 floats: no transfers

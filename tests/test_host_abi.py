@@ -199,18 +199,19 @@ def test_conv_geometry_and_argument_errors():
 
 def test_repeated_selection_is_a_table_lookup():
     """The timing model runs once per distinct problem and thread: 10^4 repeats of gemm_select on a shape whose
-    selection weighs a dozen configurations and splits must cost well under a microsecond each beyond what the
-    foreign-function call itself costs (measured on a call of the same arity that returns at its first check)."""
+    selection weighs a dozen configurations and splits must cost about a microsecond each at most beyond what the
+    foreign-function call itself costs (measured on a call of the same arity that returns at its first check),
+    and a fraction of what the same number of distinct problems costs."""
     import time
     lib = mg.load()
     kid, split = ctypes.c_int(-1), ctypes.c_int(0)
     pk, ps = ctypes.byref(kid), ctypes.byref(split)
     ws = mg.gemm_workspace_bytes(mg.F32, 49, 512, 4608)
 
-    def mean_us(dtype, reps=10000):
+    def mean_us(dtype, reps=10000, distinct=False):
         t0 = time.perf_counter()
-        for _ in range(reps):
-            lib.gemm_select(dtype, mg.COL_MAJOR, 49, 512, 4608, ws, pk, ps)
+        for i in range(reps):
+            lib.gemm_select(dtype, mg.COL_MAJOR, 49, 512, 4608 + (i if distinct else 0), ws, pk, ps)
         return (time.perf_counter() - t0) / reps * 1e6
 
     for dtype in (mg.F32, mg.F16, mg.I8):
@@ -219,7 +220,9 @@ def test_repeated_selection_is_a_table_lookup():
         floor = min(mean_us(99) for _ in range(3))             # unknown dtype: returns -1 at once
         cached = min(mean_us(dtype) for _ in range(3))
         assert (kid.value, split.value) == first
-        assert cached - floor < 0.5, "selection costs %.2f us per call beyond the call itself (%.2f)" % (cached - floor, floor)
+        modelled = min(mean_us(dtype, distinct=True) for _ in range(3))   # 10^4 keys through 256 slots: all misses
+        what = "selection costs %.2f us per repeat, %.2f us per new problem, the call itself %.2f" % (cached, modelled, floor)
+        assert cached - floor < 1.5 and cached - floor < 0.5 * (modelled - floor), what
     # the table is keyed on everything the choice depends on: another workspace size, a forced configuration
     # and a forced split each get their own answer, and the first answer comes back afterwards
     base = mg.gemm_select(mg.F32, mg.COL_MAJOR, 49, 512, 4608, ws)
