@@ -144,9 +144,12 @@ int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K,
     const int64_t ktiles = ceil_div(K, ki->BK);
     int best = 1;
     double best_us = predict_us(dtype, ki, M, N, K, 1, aligned, step_factor);
+    // the fastest split, if it beats the unsplit launch clearly (the second launch and the workspace traffic
+    // must pay for themselves)
+    const double unsplit = best_us;
     for (int s = 2; s <= kMaxAutoSplit && s <= max_split && 2 * s <= ktiles; ++s) {
         const double t = predict_us(dtype, ki, M, N, K, s, aligned, step_factor);
-        if (t < best_us * 0.92) { best_us = t; best = s; }     // a split must pay for itself clearly
+        if (t < best_us && t < unsplit * 0.92) { best_us = t; best = s; }
     }
     return best;
 }
@@ -180,7 +183,8 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
         if (!can_address(ki, lda, ldb)) continue;
         const double f = staged_orientation_factor(dtype, ki, a_kc, b_nc, aligned);
         const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned, f);
-        const double t = predict_us(dtype, ki, M, N, K, s, aligned, f);
+        double t = predict_us(dtype, ki, M, N, K, s, aligned, f);
+        if (s > 1) t *= 1.03;           // a tie between a split and an unsplit configuration goes to the unsplit one
         if (best < 0 || t < best_us) { best = id; best_us = t; }
     }
     return best < 0 ? 0 : best;

@@ -123,7 +123,9 @@ def test_timing_model_and_selection_agree():
             kid, split = mg.gemm_select(dtype, 0, M, N, K, 32 * M * N * 4)
             t = mg.gemm_predict_us(dtype, kid, M, N, K, split)
             assert t > 0
-            # forcing another configuration is never predicted to be clearly faster than the pick
+            # forcing another configuration is never predicted to be clearly faster than the pick (a split
+            # configuration must beat an unsplit one by 3 %)
+            t_eff = t * (1.03 if split > 1 else 1.0)
             for other in range(mg.gemm_kernel_count(dtype)):
                 mg.gemm_force_kernel(dtype, other, 0)
                 k2, s2 = mg.gemm_select(dtype, 0, M, N, K, 32 * M * N * 4)
@@ -133,7 +135,8 @@ def test_timing_model_and_selection_agree():
                 name = mg.gemm_kernel_name(dtype, other)
                 assert name
                 if _auto_selectable(dtype, other):
-                    assert mg.gemm_predict_us(dtype, other, M, N, K, s2) >= t * 0.999, (name, M, N, K)
+                    t2 = mg.gemm_predict_us(dtype, other, M, N, K, s2) * (1.03 if s2 > 1 else 1.0)
+                    assert t2 >= t_eff * 0.999, (name, M, N, K)
         big = mg.gemm_predict_us(dtype, 0, 4096, 4096, 4096, 1)
         assert big > mg.gemm_predict_us(dtype, 0, 2048, 2048, 2048, 1) > mg.gemm_predict_us(dtype, 0, 512, 512, 512, 1)
     with pytest.raises(mg.GemmError):
