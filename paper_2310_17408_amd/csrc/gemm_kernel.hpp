@@ -24,6 +24,7 @@
 // Transposed operands (this kernel only): A with K contiguous, element (m,k) at A[k + m*lda], and
 // B with N contiguous, element (k,n) at B[n + k*ldb].
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "gemm_table.h"
@@ -520,53 +521,50 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel(const Params p)
 
 // ---------------------------------------------------------------- helpers
 // Sum of the split-K partial tiles in fixed order, then the alpha/beta update.
-template <class acc_t>
+// VEC: every thread takes 4 consecutive elements of a column with 16-byte accesses (M and ldc multiples
+// of 4, C 16-byte aligned, C in the accumulator's type); each element is summed in the same order either way.
+template <class acc_t, bool VEC>
 __global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ ws, acc_t *__restrict__ C, int M, int N,
                                                      int64_t ldc, int split, uint32_t alpha_bits, uint32_t beta_bits,
                                                      int use_beta, int c_type)
 {
+    // int8 problems are summed as unsigned 32-bit integers (wrapping arithmetic)
+    typedef typename std::conditional<__is_same(acc_t, int), uint32_t, acc_t>::type sum_t;
+    constexpr int W = VEC ? 4 : 1;
+    typedef sum_t vec_t __attribute__((ext_vector_type(W)));
     const int64_t total = (int64_t)M * N;
-    const acc_t alpha = __builtin_bit_cast(acc_t, alpha_bits);
-    const acc_t beta = __builtin_bit_cast(acc_t, beta_bits);
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * blockDim.x) {
+    const sum_t alpha = __builtin_bit_cast(sum_t, alpha_bits);
+    const sum_t beta = __builtin_bit_cast(sum_t, beta_bits);
+    for (int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * W; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x * W) {
         const int m = (int)(idx % M);
         const int64_t n = idx / M;
-        acc_t *c = C + n * ldc + m;
         // the partial tiles are added in the order of their K slices; 8 loads are in flight at a time
-        const acc_t *src = ws + idx;
+        const vec_t *src = (const vec_t *)(ws + idx);
+        const int64_t stride = total / W;                       // vectors from one partial tile to the next
+        vec_t s = 0;
+        int zz = 0;
+        for (; zz + 8 <= split; zz += 8) {
+            vec_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(zz + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; zz < split; ++zz) s += src[(int64_t)zz * stride];
+        vec_t r = alpha * s;
         if constexpr (__is_same(acc_t, int)) {
-            uint32_t s = 0;
-            int zz = 0;
-            for (; zz + 8 <= split; zz += 8) {
-                uint32_t v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = (uint32_t)src[(int64_t)(zz + u) * total];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) s += v[u];
-            }
-            for (; zz < split; ++zz) s += (uint32_t)src[(int64_t)zz * total];
-            uint32_t r = (uint32_t)alpha * s;
-            if (use_beta) r += (uint32_t)beta * (uint32_t)(*c);
-            *c = (int)r;
+            vec_t *c = (vec_t *)(C + n * ldc + m);
+            if (use_beta) r += beta * (*c);
+            *c = r;
         } else {
-            acc_t s = 0;
-            int zz = 0;
-            for (; zz + 8 <= split; zz += 8) {
-                acc_t v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(zz + u) * total];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) s += v[u];
-            }
-            for (; zz < split; ++zz) s += src[(int64_t)zz * total];
-            acc_t r = alpha * s;
-            if (c_type == C_WIDE) {
+            if (VEC || c_type == C_WIDE) {
+                vec_t *c = (vec_t *)(C + n * ldc + m);
                 if (use_beta) r += beta * (*c);
                 *c = r;
             } else {
-                if (use_beta) r += beta * narrow_load(c_type, C, n * ldc + m);
-                narrow_store(c_type, C, n * ldc + m, r);
+                if (use_beta) r[0] += beta * narrow_load(c_type, C, n * ldc + m);
+                narrow_store(c_type, C, n * ldc + m, r[0]);
             }
         }
     }

@@ -73,13 +73,24 @@ static unsigned blocks_for(int64_t total)
 hipError_t launch_reduce(int dtype, const void *ws, void *C, int M, int N, int64_t ldc, int split,
                          uint32_t alpha_bits, uint32_t beta_bits, int use_beta, hipStream_t stream, int c_type)
 {
-    const unsigned g = blocks_for((int64_t)M * N);
-    if (dtype == 2)
-        hipLaunchKernelGGL(reduce_kernel<int>, dim3(g), dim3(256), 0, stream, (const int *)ws, (int *)C, M, N, ldc,
-                           split, alpha_bits, beta_bits, use_beta, C_WIDE);
-    else
-        hipLaunchKernelGGL(reduce_kernel<float>, dim3(g), dim3(256), 0, stream, (const float *)ws, (float *)C, M, N,
-                           ldc, split, alpha_bits, beta_bits, use_beta, c_type);
+    const bool vec = M % 4 == 0 && ldc % 4 == 0 && (uintptr_t)C % 16 == 0 && (uintptr_t)ws % 16 == 0 &&
+                     (dtype == 2 || c_type == C_WIDE);
+    const unsigned g = blocks_for(vec ? (int64_t)M * N / 4 : (int64_t)M * N);
+    if (dtype == 2) {
+        if (vec)
+            hipLaunchKernelGGL((reduce_kernel<int, true>), dim3(g), dim3(256), 0, stream, (const int *)ws, (int *)C, M, N, ldc,
+                               split, alpha_bits, beta_bits, use_beta, C_WIDE);
+        else
+            hipLaunchKernelGGL((reduce_kernel<int, false>), dim3(g), dim3(256), 0, stream, (const int *)ws, (int *)C, M, N, ldc,
+                               split, alpha_bits, beta_bits, use_beta, C_WIDE);
+    } else {
+        if (vec)
+            hipLaunchKernelGGL((reduce_kernel<float, true>), dim3(g), dim3(256), 0, stream, (const float *)ws, (float *)C, M, N,
+                               ldc, split, alpha_bits, beta_bits, use_beta, c_type);
+        else
+            hipLaunchKernelGGL((reduce_kernel<float, false>), dim3(g), dim3(256), 0, stream, (const float *)ws, (float *)C, M, N,
+                               ldc, split, alpha_bits, beta_bits, use_beta, c_type);
+    }
     return hipGetLastError();
 }
 

@@ -64,7 +64,7 @@ def _check(dtype, layout, M, N, K, alpha, beta, seed, want_split):
 def test_two_calls_in_a_row_second_smaller(dtype, alpha, beta):
     # deep K, few output tiles: the selector splits K over workgroups and the partial tiles go to the array
     _check(dtype, "col", 49, 512, 4608, alpha, beta, 9100, want_split=True)
-    _check(dtype, "col", 33, 64, 2304, alpha, beta, 9200, want_split=(dtype != "f32"))
+    _check(dtype, "col", 33, 64, 4608, alpha, beta, 9200, want_split=True)
     # and a problem that does not split at all (no scratch used) after those
     _check(dtype, "row", 200, 300, 150, alpha, beta, 9300, want_split=False)
 
