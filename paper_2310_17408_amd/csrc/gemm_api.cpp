@@ -8,6 +8,7 @@
 #include <limits.h>
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 using namespace mig;
@@ -351,6 +352,8 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     p.b_nc = b_nc ? 1 : 0;
     p.group_m = 8;
     p.xcd_remap = ((int64_t)p.tiles_m * p.tiles_n >= 64) ? 1 : 0;
+    if (const char *e = getenv("MIG_GROUP_M")) p.group_m = atoi(e);   // EXPERIMENT
+    if (const char *e = getenv("MIG_XCD")) p.xcd_remap = atoi(e);     // EXPERIMENT
     p.c_type = c_type;
 
     hipError_t e = ki->launch(p, stream);

@@ -122,6 +122,16 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane % BS, g = lane / BS;
+    // Which elements of B (rows n with K contiguous) a lane loads.  In the MFMA layout neighbouring lanes hold
+    // neighbouring rows, and a 16-byte load per lane then touches 64 different 64-byte pieces of memory per
+    // instruction; the vector cache takes them one per cycle, which is what bounds these kernels.  With 16 x 16
+    // blocks a K step is 64 bytes of a row: four neighbouring lanes load the four 16-byte chunks of one row (16
+    // pieces per instruction), and each value is moved to the lane that multiplies it just before its MFMAs.
+    constexpr bool COAL = (BS == 16) && (IM2ROW != IM2ROW_RUNS);
+    static_assert(!COAL || KG == 4, "a lane loads one 16-byte chunk per block column");
+    const int rb = COAL ? lane / 4 : r;                        // row of a block whose elements this lane loads
+    const int gb = COAL ? lane % 4 : g;                        // and which KG consecutive k of it
+    const int b_from = (4 * r + g) * 4;                        // COAL: byte index of the lane that loaded this lane's operands
 
     int tm, tn;
     tile_coords(p, blockIdx.x, tm, tn);
@@ -168,7 +178,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
     const int run = p.conv.kw * p.conv.Cin;                    // IM2ROW_RUNS: elements of K per filter row
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        int n = nw + BS * j + r;
+        int n = nw + BS * j + rb;
         n = n < p.N ? n : p.N - 1;
         if constexpr (IM2ROW) {
             const int per_image = p.conv.Hout * p.conv.Wout;
@@ -185,9 +195,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
             }
             // from the address the tap (0, 0) of a pixel at (0, 0) without padding would have: never negative
             boff[j] = (uint32_t)((((int64_t)(b * p.conv.H + oh * p.conv.stride_h) * p.conv.W + ow * p.conv.stride_w) *
-                                      p.conv.Cin + (IM2ROW == IM2ROW_TAPS ? KG * g : 0)) * 4);
+                                      p.conv.Cin + (IM2ROW == IM2ROW_TAPS ? KG * gb : 0)) * 4);
         } else {
-            boff[j] = (uint32_t)(((int64_t)(n - nw) * p.ldb + KG * g) * 4);
+            boff[j] = (uint32_t)(((int64_t)(n - nw) * p.ldb + KG * gb) * 4);
         }
     }
     const MIG_GLOBAL unsigned char *a_wave =
@@ -314,8 +324,9 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
                 xa.v[t][i] = valid ? *(const MIG_GLOBAL float *)(ta_ + t * a_row + off) : 0.0f;
             }
             if constexpr (IM2ROW == IM2ROW_NONE) {
+                const bool valid_b = (KG * gb + t) < tail;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) xb.v[j][t] = valid ? *(const MIG_GLOBAL float *)(tb_ + boff[j] + 4 * t) : 0.0f;
+                for (int j = 0; j < TN; ++j) xb.v[j][t] = valid_b ? *(const MIG_GLOBAL float *)(tb_ + boff[j] + 4 * t) : 0.0f;
             }
         }
         if constexpr (IM2ROW == IM2ROW_RUNS) load_b_runs(k_begin + nfull * BK + KG * g, xb);
@@ -331,6 +342,18 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
 
     aset fa[D], ta;
     bset fb[D], tb;
+    // the MFMAs of one step; COAL: its B operands first move from the lanes that loaded them to the lanes of the
+    // MFMA layout (a permutation of the wave's lanes through the LDS crossbar, no memory involved)
+    auto mma_step = [&](const aset &xa, bset &xb) __attribute__((always_inline)) {
+        if constexpr (COAL) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int t = 0; t < KG; ++t)
+                    xb.v[j][t] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(b_from, __builtin_bit_cast(int, xb.v[j][t])));
+        }
+        Micro::mma(xa, xb, acc);
+    };
     if (tail) load_tail(ta, tb);                               // the first loads to be issued
 
     // ---- K loop: D steps in flight.  In the steady state every load is unconditional, so the
@@ -341,10 +364,10 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
 #pragma unroll
             for (int d = 0; d < D; ++d)
                 if (d < nfull) load_step(one_by_one, fa[d], fb[d]);
-            if (tail) Micro::mma(ta, tb, acc);
+            if (tail) mma_step(ta, tb);
 #pragma unroll
             for (int d = 0; d < D; ++d)
-                if (d < nfull) Micro::mma(fa[d], fb[d], acc);
+                if (d < nfull) mma_step(fa[d], fb[d]);
             return;
         }
 #pragma unroll
@@ -352,13 +375,13 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
             load_step(one_by_one, fa[d], fb[d]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (tail) Micro::mma(ta, tb, acc);                     // its operands are the oldest loads
+        if (tail) mma_step(ta, tb);                     // its operands are the oldest loads
         __builtin_amdgcn_sched_barrier(0);
         int s = 0;
         for (; s + 2 * D <= nfull; s += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                Micro::mma(fa[d], fb[d], acc);
+                mma_step(fa[d], fb[d]);
                 load_step(one_by_one, fa[d], fb[d]);
                 __builtin_amdgcn_sched_barrier(0);             // keep the steps apart: one wait per step
             }
@@ -367,13 +390,13 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         const int rest = nfull - s - D;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            Micro::mma(fa[d], fb[d], acc);
+            mma_step(fa[d], fb[d]);
             if (d < rest) load_step(one_by_one, fa[d], fb[d]);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            if (d < rest) Micro::mma(fa[d], fb[d], acc);
+            if (d < rest) mma_step(fa[d], fb[d]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -381,7 +404,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
         if (a_rows_one_by_one) k_loop(std::integral_constant<bool, true>());
         else k_loop(std::integral_constant<bool, false>());
     } else if (tail) {
-        Micro::mma(ta, tb, acc);
+        mma_step(ta, tb);
     }
 
     // ---- the waves that share this tile hand their partial tiles to the first of them
