@@ -129,9 +129,11 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
     // pieces per instruction), and each value is moved to the lane that multiplies it just before its MFMAs.
     constexpr bool COAL = (BS == 16) && (IM2ROW != IM2ROW_RUNS);
     static_assert(!COAL || KG == 4, "a lane loads one 16-byte chunk per block column");
+    // (rows 8 ... 15 take their chunks in the order 2, 3, 0, 1: the permutation then reads 32 different banks per
+    // half wave)
     const int rb = COAL ? lane / 4 : r;                        // row of a block whose elements this lane loads
-    const int gb = COAL ? lane % 4 : g;                        // and which KG consecutive k of it
-    const int b_from = (4 * r + g) * 4;                        // COAL: byte index of the lane that loaded this lane's operands
+    const int gb = COAL ? (lane % 4) ^ ((lane >> 5) << 1) : g; // and which KG consecutive k of it
+    const int b_from = (4 * r + (g ^ ((r >> 3) << 1))) * 4;    // COAL: byte index of the lane that loaded this lane's operands
 
     int tm, tn;
     tile_coords(p, blockIdx.x, tm, tn);
