@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(T::NT, T::MINB) gemm_kernel_reg32(const Params
     const int r = lane % BS, g = lane / BS;
     // Which elements of B (rows n with K contiguous) a lane loads.  In the MFMA layout neighbouring lanes hold
     // neighbouring rows, and a 16-byte load per lane then touches 64 different 64-byte pieces of memory per
-    // instruction; the vector cache takes them one per cycle, which is what bounds these kernels.  With 16 x 16
+    // instruction, which the vector cache takes one per cycle (measured: 4-8 % of the run time).  With 16 x 16
     // blocks a K step is 64 bytes of a row: four neighbouring lanes load the four 16-byte chunks of one row (16
     // pieces per instruction), and each value is moved to the lane that multiplies it just before its MFMAs.
     constexpr bool COAL = (BS == 16) && (IM2ROW != IM2ROW_RUNS);
