@@ -1,5 +1,7 @@
 // fp32 workgroup-tile GEMM kernel with global -> LDS transfers for transposed operands (gemm_ex): A with K
-// contiguous (A_KC) and / or B with N contiguous (B_NC).  The canonical orientation is served by
+// contiguous (A_KC) and / or B with N contiguous (B_NC).  As in the canonical kernel the transfers are the
+// packing step (Pack A / Pack B of the paper's Fig. "Pseudo-code of the BLIS base GEMM algorithm") and the
+// MFMA chain on fragments read from LDS is its micro-kernel (Sec. "Micro-kernel Generation").  The canonical orientation is served by
 // gemm_kernel_dma32.hpp, whose tile geometry (Dma32Tile), transfers and stage layout this kernel shares.
 //
 // An fp32 MFMA fragment is one float per lane, so no operand ever needs a transpose: each one is staged as
