@@ -126,9 +126,10 @@ int gemm_i8(int layout, int64_t M, int64_t N, int64_t K,
  * aside when it fixes row-major C code with C^T = B^T A^T.  alpha and beta are
  * host pointers to a float (fp32, fp16, bf16) or an int32 (int8).  With
  * transa = transb = 0 the call is gemm_f32 / gemm_f16 / gemm_i8 / gemm_bf16;
- * for fp16 / bf16 / int8 every combination runs on the direct kernels at about their normal speed
- * (a K-contiguous A is staged like B, an N-contiguous B like A; the latter on the square tiles),
- * for fp32 the transposed combinations run on the staged kernels.  Same ownership, stream and
+ * every combination runs on the direct kernels at about their normal speed when the rows of the
+ * operands are 16-byte aligned (a K-contiguous A is staged like B, an N-contiguous B like A; for
+ * fp16 / bf16 / int8 the latter on the square tiles); fp32 operands whose rows are not 16-byte
+ * aligned go through the staged kernels or the guarded path of the direct ones.  Same ownership, stream and
  * workspace rules; status -k names the k-th argument of this list
  * (gemm_ex_status_string gives the text). */
 int gemm_ex(int dtype, int layout, int transa, int transb, int64_t M, int64_t N, int64_t K,
