@@ -15,7 +15,7 @@ using namespace mig;
 
 namespace {
 
-constexpr int NUM_CU = 256;      // MI355X compute units
+constexpr int kChipCu = 256;     // compute units of a whole MI355X: the part the rate constants below were measured on
 constexpr int MAX_SPLIT = 32;    // upper limit of the K split
 
 struct Forced { int id = -1; int split = 0; };
@@ -62,7 +62,20 @@ constexpr double kGuardedStepFactor = 2.2;
 constexpr double kReduceBytesPerUs = 4.0e6;
 constexpr double kLaunchUs = 2.5, kReduceLaunchUs = 3.0;
 constexpr int kMaxAutoSplit = 16;
-constexpr int NUM_SIMD = 4 * NUM_CU;
+
+// Compute units of the device the model plans for: read once per process from the device that is current at the
+// first call (a partition of the chip has fewer than the whole part); 256 when no device can be asked.
+int num_cu()
+{
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            return v;
+        return kChipCu;
+    }();
+    return n;
+}
 
 // How much longer a K step of a staged fp32 kernel takes when B has N contiguous (its tile goes through
 // the register transposes and, with bank conflicts, into LDS), alone or together with a K-contiguous A:
@@ -90,19 +103,21 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
     const double ktiles = (double)ceil_div(K, ki->BK);
     const double steps = (double)ceil_div((int64_t)ktiles, split);
     const double eff = (ki->eff_pct > 0 ? ki->eff_pct : 100) / 100.0;
+    const int NUM_CU = num_cu();
+    const double part = (double)NUM_CU / kChipCu;             // share of the whole chip's MFMA and fill rates
     double main_us;
     if (ki->waves_k > 0) {
         const double wave_tiles = tiles * (ki->BM / ki->wave_m) * (ki->BN / ki->wave_n);
         const double waves = wave_tiles * ki->waves_k * split;
-        double rounds = waves / ((double)NUM_SIMD * ki->waves_per_simd);
+        double rounds = waves / (4.0 * NUM_CU * ki->waves_per_simd);
         if (rounds < 1.0) rounds = 1.0;
         const double steps_per_wave = (double)ceil_div((int64_t)steps, ki->waves_k);
         const double chain = rounds * steps_per_wave * ki->step_floor_ns * 1e-3;
         const double mfma = 2.0 * wave_tiles * ki->wave_m * ki->wave_n * ktiles * ki->BK /
-                            (kSustainedTflops[dtype] * 1e6 * eff);
+                            (kSustainedTflops[dtype] * 1e6 * eff * part);
         // the fill rate is a sum over CUs: with fewer workgroups than CUs less of it is there (measured:
         // about the square root of the busy share, since a CU alone in its part of the chip fills faster)
-        const double busy = tiles * split < NUM_CU ? sqrt(tiles * split / NUM_CU) : 1.0;
+        const double busy = (tiles * split < NUM_CU ? sqrt(tiles * split / NUM_CU) : 1.0) * part;
         const double fill = wave_tiles * ktiles * (double)(ki->wave_m + ki->wave_n) * ki->BK * es[dtype] /
                             (ki->fill_bytes_per_us * busy);
         main_us = chain > mfma ? chain : mfma;
@@ -110,7 +125,7 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
     } else {
         const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
         const double wgs = tiles * split;
-        const double mfma_step = step_factor * 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / NUM_CU) / eff;
+        const double mfma_step = step_factor * 2.0 * ki->BM * ki->BN * ki->BK / (kSustainedTflops[dtype] * 1e6 / kChipCu) / eff;
         double floor_us = step_factor * (ki->step_floor_ns > 0 ? ki->step_floor_ns * 1e-3 : kStepFloorUs);
         if (M < ki->BM || N < ki->BN) floor_us *= kGuardedStepFactor;
         // time of one K step on a CU that runs `resident` workgroups side by side
@@ -131,7 +146,7 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
             main_us += steps * step_us((double)ceil_div((int64_t)rest, NUM_CU));
         }
         const double staged = tiles * ktiles * (double)(ki->BM + ki->BN) * ki->BK * es[dtype];
-        if (main_us < staged / kStagingBytesPerUs) main_us = staged / kStagingBytesPerUs;
+        if (main_us < staged / (kStagingBytesPerUs * part)) main_us = staged / (kStagingBytesPerUs * part);
     }
     double reduce_us = 0.0;
     if (split > 1) reduce_us = kReduceLaunchUs + (double)split * (double)M * (double)N * 8.0 / kReduceBytesPerUs;
