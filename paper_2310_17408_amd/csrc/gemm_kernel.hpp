@@ -571,29 +571,30 @@ __global__ void __launch_bounds__(256) reduce_kernel(const acc_t *__restrict__ w
 }
 
 // C <- beta*C (K == 0 or alpha == 0); beta == 0 stores zeros without reading C.
-template <class acc_t>
+// VEC: 4 consecutive elements of a column per thread with 16-byte accesses (conditions as for reduce_kernel).
+template <class acc_t, bool VEC>
 __global__ void __launch_bounds__(256) scale_kernel(acc_t *__restrict__ C, int M, int N, int64_t ldc,
                                                     uint32_t beta_bits, int use_beta, int c_type)
 {
+    typedef typename std::conditional<__is_same(acc_t, int), uint32_t, acc_t>::type sum_t;
+    constexpr int W = VEC ? 4 : 1;
+    typedef sum_t vec_t __attribute__((ext_vector_type(W)));
     const int64_t total = (int64_t)M * N;
-    const acc_t beta = __builtin_bit_cast(acc_t, beta_bits);
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * blockDim.x) {
+    const sum_t beta = __builtin_bit_cast(sum_t, beta_bits);
+    for (int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * W; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x * W) {
         const int m = (int)(idx % M);
         const int64_t n = idx / M;
-        acc_t *c = C + n * ldc + m;
-        if constexpr (!__is_same(acc_t, int)) {
+        if constexpr (!__is_same(acc_t, int) && !VEC) {
             if (c_type != C_WIDE) {
                 narrow_store(c_type, C, n * ldc + m, use_beta ? beta * narrow_load(c_type, C, n * ldc + m) : 0.0f);
                 continue;
             }
         }
-        if (use_beta) {
-            if constexpr (__is_same(acc_t, int)) *c = (int)((uint32_t)beta * (uint32_t)(*c));
-            else *c = beta * (*c);
-        } else {
-            *c = 0;
-        }
+        vec_t *c = (vec_t *)(C + n * ldc + m);
+        vec_t v = 0;
+        if (use_beta) v = beta * (*c);
+        *c = v;
     }
 }
 

@@ -65,7 +65,7 @@ const KernelInfo *kernel_info(int dtype, int id)
 static unsigned blocks_for(int64_t total)
 {
     int64_t b = (total + 255) / 256;
-    if (b > 8192) b = 8192;
+    if (b > (1 << 20)) b = 1 << 20;                  // measured: grid-stride loops of many rounds stream slower
     if (b < 1) b = 1;
     return (unsigned)b;
 }
@@ -110,12 +110,15 @@ hipError_t launch_im2row_matrix(int es, const void *image, void *matrix, int64_t
 hipError_t launch_scale(int dtype, void *C, int M, int N, int64_t ldc, uint32_t beta_bits, int use_beta,
                         hipStream_t stream, int c_type)
 {
-    const unsigned g = blocks_for((int64_t)M * N);
-    if (dtype == 2)
-        hipLaunchKernelGGL(scale_kernel<int>, dim3(g), dim3(256), 0, stream, (int *)C, M, N, ldc, beta_bits, use_beta, C_WIDE);
-    else
-        hipLaunchKernelGGL(scale_kernel<float>, dim3(g), dim3(256), 0, stream, (float *)C, M, N, ldc, beta_bits,
-                           use_beta, c_type);
+    const bool vec = M % 4 == 0 && ldc % 4 == 0 && (uintptr_t)C % 16 == 0 && (dtype == 2 || c_type == C_WIDE);
+    const unsigned g = blocks_for(vec ? (int64_t)M * N / 4 : (int64_t)M * N);
+    if (dtype == 2) {
+        if (vec) hipLaunchKernelGGL((scale_kernel<int, true>), dim3(g), dim3(256), 0, stream, (int *)C, M, N, ldc, beta_bits, use_beta, C_WIDE);
+        else hipLaunchKernelGGL((scale_kernel<int, false>), dim3(g), dim3(256), 0, stream, (int *)C, M, N, ldc, beta_bits, use_beta, C_WIDE);
+    } else {
+        if (vec) hipLaunchKernelGGL((scale_kernel<float, true>), dim3(g), dim3(256), 0, stream, (float *)C, M, N, ldc, beta_bits, use_beta, c_type);
+        else hipLaunchKernelGGL((scale_kernel<float, false>), dim3(g), dim3(256), 0, stream, (float *)C, M, N, ldc, beta_bits, use_beta, c_type);
+    }
     return hipGetLastError();
 }
 
