@@ -81,13 +81,19 @@ int num_cu()
 // the register transposes and, with bank conflicts, into LDS), alone or together with a K-contiguous A:
 // measured at 1024^3 ... 4096^3, the smaller the tile the more.  1 for every other kernel, data type and
 // orientation (the 16- and 8-bit types have direct kernels for these orientations).
-double staged_orientation_factor(int dtype, const KernelInfo *ki, bool a_kc, bool b_nc, bool aligned = true)
+// How operands are aligned, as far as the kernels care: ALIGN_FULL = the rows of both canonical operands are
+// 16-byte aligned (vector loads, global -> LDS transfers); ALIGN_WORDS = the K-contiguous operand's rows are, and
+// the rows of the M-contiguous one are 4-byte aligned (what the 16- and 8-bit register-direct kernels load: 16-byte
+// fragments of the one, 32-bit words of the other); ALIGN_NONE = neither.
+enum { ALIGN_NONE = 0, ALIGN_WORDS = 1, ALIGN_FULL = 2 };
+
+double staged_orientation_factor(int dtype, const KernelInfo *ki, bool a_kc, bool b_nc, int align = ALIGN_FULL)
 {
     if (dtype != MI_GEMM_F32 || !(a_kc || b_nc)) return 1.0;
     // the direct fp32 kernels take transposed operands at their normal speed when rows are 16-byte aligned;
     // otherwise every tile of theirs goes through guarded loads and registers (measured 2.2 ... 3.2 times
     // slower at 2050^3 and 1026^3, against which the staged kernels' factors below compete)
-    if (!ki->transposed_ok) return aligned ? 1.0 : 2.6;
+    if (!ki->transposed_ok) return align == ALIGN_FULL ? 1.0 : 2.6;
     if (!b_nc) return 1.0;
     const int area = ki->BM * ki->BN;
     if (area <= 64 * 64) return a_kc ? 1.85 : 2.6;
@@ -95,7 +101,7 @@ double staged_orientation_factor(int dtype, const KernelInfo *ki, bool a_kc, boo
     return a_kc ? 1.15 : 1.45;
 }
 
-double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split, bool aligned = true,
+double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int split, int align = ALIGN_FULL,
                   double step_factor = 1.0)
 {
     static const int es[NUM_DTYPES] = {4, 2, 1, 2};
@@ -122,6 +128,11 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
                             (ki->fill_bytes_per_us * busy);
         main_us = chain > mfma ? chain : mfma;
         if (fill > main_us) main_us = fill;
+        // operands whose rows are not 16-byte aligned: the 16- and 8-bit kernels issue their 4- and 16-byte loads
+        // at element alignment and the memory system splits them.  The step constants were fitted over aligned
+        // and ragged shapes alike, so this is the part of the slowdown they do not carry (tiny ragged shapes
+        // measure 2 ... 3 times the K loop of their aligned twins, large ones 1.1 ... 1.9 times)
+        if (align == ALIGN_NONE && ki->unaligned_pct > 0) main_us *= 100.0 / ki->unaligned_pct;
     } else {
         const int occ = ki->min_blocks_per_cu > 0 ? ki->min_blocks_per_cu : 1;
         const double wgs = tiles * split;
@@ -132,7 +143,7 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
         auto step_us = [&](double resident) {
             double step = resident * mfma_step;
             if (step < floor_us) step = floor_us;
-            if (!aligned && ki->unaligned_pct > 0) step *= 100.0 / ki->unaligned_pct;
+            if (align != ALIGN_FULL && ki->unaligned_pct > 0) step *= 100.0 / ki->unaligned_pct;
             return step;
         };
         // whole rounds with every slot of every CU taken, then the rest: fewer workgroups per CU, each of
@@ -154,17 +165,17 @@ double predict_us(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t
 }
 
 // Best split for one configuration (used directly when the configuration is forced).
-int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split, bool aligned = true,
+int auto_split(int dtype, const KernelInfo *ki, int64_t M, int64_t N, int64_t K, int64_t max_split, int align = ALIGN_FULL,
                double step_factor = 1.0)
 {
     const int64_t ktiles = ceil_div(K, ki->BK);
     int best = 1;
-    double best_us = predict_us(dtype, ki, M, N, K, 1, aligned, step_factor);
+    double best_us = predict_us(dtype, ki, M, N, K, 1, align, step_factor);
     // the fastest split, if it beats the unsplit launch clearly (the second launch and the workspace traffic
     // must pay for themselves)
     const double unsplit = best_us;
     for (int s = 2; s <= kMaxAutoSplit && s <= max_split && 2 * s <= ktiles; ++s) {
-        const double t = predict_us(dtype, ki, M, N, K, s, aligned, step_factor);
+        const double t = predict_us(dtype, ki, M, N, K, s, align, step_factor);
         if (t < best_us && t < unsplit * 0.92) { best_us = t; best = s; }
     }
     return best;
@@ -178,7 +189,7 @@ bool can_address(const KernelInfo *ki, int64_t lda, int64_t ldb)
 
 // Best (configuration, split) over the configurations open to automatic selection (prio > 0).
 int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t max_split_bytes_per_mn,
-                bool aligned, bool a_kc, bool b_nc)
+                int align, bool a_kc, bool b_nc)
 {
     const int n = kernel_count(dtype);
     int best = -1;
@@ -197,26 +208,26 @@ int auto_kernel(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
                                            : ki->transposed_ok != 0;
         if (!takes) continue;
         if (!can_address(ki, lda, ldb)) continue;
-        const double f = staged_orientation_factor(dtype, ki, a_kc, b_nc, aligned);
-        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, aligned, f);
-        double t = predict_us(dtype, ki, M, N, K, s, aligned, f);
+        const double f = staged_orientation_factor(dtype, ki, a_kc, b_nc, align);
+        const int s = auto_split(dtype, ki, M, N, K, max_split_bytes_per_mn, align, f);
+        double t = predict_us(dtype, ki, M, N, K, s, align, f);
         if (s > 1) t *= 1.03;           // a tie between a split and an unsplit configuration goes to the unsplit one
         if (best < 0 || t < best_us) { best = id; best_us = t; }
     }
     return best < 0 ? 0 : best;
 }
 
-Choice choose_uncached(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t fit, bool aligned,
+Choice choose_uncached(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t fit, int align,
                        bool a_kc, bool b_nc, const Forced f)
 {
     Choice c;
     const bool forced = f.id >= 0 && f.id < kernel_count(dtype) && can_address(kernel_info(dtype, f.id), lda, ldb) &&
                         (!(a_kc || b_nc) || kernel_info(dtype, f.id)->transposed_ok ||
                          ((!a_kc || kernel_info(dtype, f.id)->a_kc_ok) && (!b_nc || kernel_info(dtype, f.id)->b_nc_ok)));
-    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc);
+    c.id = forced ? f.id : auto_kernel(dtype, M, N, K, lda, ldb, fit, align, a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, c.id);
     const int64_t ktiles = ceil_div(K, ki->BK);
-    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, aligned, staged_orientation_factor(dtype, ki, a_kc, b_nc, aligned));
+    int64_t s = f.split >= 1 ? f.split : auto_split(dtype, ki, M, N, K, fit, align, staged_orientation_factor(dtype, ki, a_kc, b_nc, align));
     if (s > ktiles) s = ktiles;
     if (s > fit) s = fit;
     if (s < 1) s = 1;
@@ -232,7 +243,7 @@ Choice choose_uncached(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, 
 struct ChoiceKey {
     int64_t M, N, K;
     int32_t forced_split;
-    uint32_t bits;      // dtype, aligned, a_kc, b_nc, fit, forced id + 1
+    uint32_t bits;      // dtype, alignment class, a_kc, b_nc, fit, forced id + 1
     bool operator==(const ChoiceKey &o) const
     {
         return M == o.M && N == o.N && K == o.K && forced_split == o.forced_split && bits == o.bits;
@@ -262,7 +273,7 @@ int64_t addressing_limit(int dtype)
 }
 
 Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, size_t ws_bytes, bool have_ws,
-              bool aligned, bool a_kc = false, bool b_nc = false)
+              int align, bool a_kc = false, bool b_nc = false)
 {
     const Forced f = t_forced[dtype];
     // how many partial tiles the workspace can hold
@@ -271,20 +282,27 @@ Choice choose(int dtype, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t l
     if (fit > MAX_SPLIT) fit = MAX_SPLIT;
     if (fit < 1) fit = 1;
     const int64_t limit = addressing_limit(dtype);
-    if (lda > limit || ldb > limit || f.id >= 254) return choose_uncached(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc, f);
+    if (lda > limit || ldb > limit || f.id >= 254) return choose_uncached(dtype, M, N, K, lda, ldb, fit, align, a_kc, b_nc, f);
     ChoiceKey key;
     key.M = M; key.N = N; key.K = K;
     key.forced_split = f.split;
-    key.bits = (uint32_t)dtype | (aligned ? 4u : 0u) | (a_kc ? 8u : 0u) | (b_nc ? 16u : 0u) | ((uint32_t)fit << 5) |
-               ((uint32_t)(f.id + 1) << 11);
+    key.bits = (uint32_t)dtype | ((uint32_t)align << 2) | (a_kc ? 16u : 0u) | (b_nc ? 32u : 0u) | ((uint32_t)fit << 6) |
+               ((uint32_t)(f.id + 1) << 12);
     uint64_t h = (uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^ (uint64_t)K * 0x165667B19E3779F9ull ^
                  ((uint64_t)key.bits << 32 | (uint32_t)key.forced_split) * 0xD6E8FEB86659FD93ull;
     ChoiceSlot &slot = t_choice[(h >> 40) % kChoiceSlots];
     if (slot.used && slot.key == key) return slot.choice;
-    slot.choice = choose_uncached(dtype, M, N, K, lda, ldb, fit, aligned, a_kc, b_nc, f);
+    slot.choice = choose_uncached(dtype, M, N, K, lda, ldb, fit, align, a_kc, b_nc, f);
     slot.key = key;
     slot.used = true;
     return slot.choice;
+}
+
+// Alignment class of a canonical problem: rows of A (M contiguous unless a_kc) and of B (K contiguous unless b_nc)
+int alignment_class(bool vec_a, bool vec_b, bool a_words, bool a_kc, bool b_nc)
+{
+    if (vec_a && vec_b) return ALIGN_FULL;
+    return (!a_kc && !b_nc && vec_b && a_words) ? ALIGN_WORDS : ALIGN_NONE;
 }
 
 bool aligned16(const void *p, int64_t ld, int es)
@@ -344,7 +362,9 @@ int run(int dtype, int es, int layout, int64_t M, int64_t N, int64_t K, uint32_t
     }
 
     const bool vec_a = aligned16(Ac, ldac, es), vec_b = aligned16(Bc, ldbc, es);
-    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr, vec_a && vec_b, a_kc, b_nc);
+    const bool a_words = (uintptr_t)Ac % 4 == 0 && (ldac * es) % 4 == 0;
+    const Choice ch = choose(dtype, Mc, Nc, K, ldac, ldbc, ws_bytes, ws != nullptr,
+                             alignment_class(vec_a, vec_b, a_words, a_kc, b_nc), a_kc, b_nc);
     const KernelInfo *ki = kernel_info(dtype, ch.id);
 
     Params p;
@@ -670,11 +690,11 @@ size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K)
     for (int id = 0; id < kernel_count(dtype); ++id) {
         const KernelInfo *ki = kernel_info(dtype, id);
         for (int o = 0; o < 4; ++o) {
-            for (int aligned = 0; aligned < 2; ++aligned) {
-                const double f = staged_orientation_factor(dtype, ki, kOrient[o][0], kOrient[o][1], aligned != 0);
+            for (int align = ALIGN_NONE; align <= ALIGN_FULL; ++align) {
+                const double f = staged_orientation_factor(dtype, ki, kOrient[o][0], kOrient[o][1], align);
                 if (o > 0 && f == 1.0) continue;                // as the canonical orientation
-                const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT, aligned != 0, f);
-                const int64_t s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT, aligned != 0, f);
+                const int64_t s1 = auto_split(dtype, ki, M, N, K, MAX_SPLIT, align, f);
+                const int64_t s2 = auto_split(dtype, ki, N, M, K, MAX_SPLIT, align, f);
                 if (s1 > smax) smax = s1;
                 if (s2 > smax) smax = s2;
             }
@@ -764,8 +784,8 @@ int gemm_select(int dtype, int layout, int64_t M, int64_t N, int64_t K, size_t w
     // canonical B has K contiguous
     static const int es[NUM_DTYPES] = {4, 2, 1, 2};
     const int64_t Mc = col ? M : N, Nc = col ? N : M;
-    const bool aligned = (Mc * es[dtype]) % 16 == 0 && (K * es[dtype]) % 16 == 0;
-    const Choice ch = choose(dtype, Mc, Nc, K, Mc, K, workspace_bytes, workspace_bytes > 0, aligned);
+    const int align = alignment_class((Mc * es[dtype]) % 16 == 0, (K * es[dtype]) % 16 == 0, (Mc * es[dtype]) % 4 == 0, false, false);
+    const Choice ch = choose(dtype, Mc, Nc, K, Mc, K, workspace_bytes, workspace_bytes > 0, align);
     if (kernel_id) *kernel_id = ch.id;
     if (split) *split = ch.split;
     return 0;
@@ -777,8 +797,8 @@ double gemm_predict_us(int dtype, int id, int64_t M, int64_t N, int64_t K, int s
     if (!ki || M <= 0 || N <= 0 || K <= 0 || split <= 0 || M > INT_MAX || N > INT_MAX || K > INT_MAX) return -1.0;
     // as gemm_select for a column-major problem: tight leading dimensions, aligned base addresses
     static const int es[NUM_DTYPES] = {4, 2, 1, 2};
-    const bool aligned = (M * es[dtype]) % 16 == 0 && (K * es[dtype]) % 16 == 0;
-    return predict_us(dtype, ki, M, N, K, split, aligned);
+    const int align = alignment_class((M * es[dtype]) % 16 == 0, (K * es[dtype]) % 16 == 0, (M * es[dtype]) % 4 == 0, false, false);
+    return predict_us(dtype, ki, M, N, K, split, align);
 }
 
 int gemm_solo(int dtype, int id, int workgroups, int ksteps, int fill, void *stream)

@@ -311,11 +311,11 @@ static hipError_t solo_reg16(int wg, int ks, int fill, hipStream_t st)
 }
 template <class T>
 static constexpr KernelInfo info_reg16(const char *name, int prio, int eff_pct, int step_ns, int setup_ns,
-                                       int waves_per_simd, double fill_bytes_per_us)
+                                       int waves_per_simd, double fill_bytes_per_us, int unaligned_pct = 80)
 {
     return KernelInfo{name, T::BM, T::BN, T::BK, T::NT, T::LDS_BYTES, &launch_tile_reg16<T>, prio, eff_pct, step_ns, setup_ns,
                       &solo_reg16<T>, T::MINB, T::MAX_LDA, T::MAX_LDB, T::WM, T::WN, T::WAVES_K, waves_per_simd,
-                      fill_bytes_per_us, 30, 0, &launch_tile_reg16_im2row<T>, nullptr};
+                      fill_bytes_per_us, unaligned_pct, 0, &launch_tile_reg16_im2row<T>, nullptr};
 }
 
 template <class T>
