@@ -76,6 +76,6 @@ def test_roofline_is_the_dominant_kernels_own_rate():
     assert abs(r["frac"] - r["achieved"] / 157.3) < 1e-4
     assert abs(r["avg_launch_ms"] - (0.958 + 7.4) / 2) < 1e-4
     # counter figure: the mean over that kernel's launches, null as soon as an unprofiled kernel is selected
-    assert abs(r["traffic"] - (844.2e6 + 67.1e6 + 6687.3e6 + 268.4e6) / 2) < 1.0
+    assert abs(r["traffic"] - (844.2e6 + 67.1e6 + 6684.6e6 + 268.4e6) / 2) < 1.0
     other = [("f32_new_kernel", n, f, ms) for (_, n, f, ms) in _fake_launches(steps=1)]
     assert bench.roofline_of_dominant_kernel(other)["traffic"] is None
